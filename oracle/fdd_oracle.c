@@ -1,0 +1,212 @@
+/*
+ * fdd_oracle.c -- TEST INFRASTRUCTURE, NOT THE PRODUCT.
+ *
+ * A plain, slow, fp64 CPU statement of what one denoising step of a
+ * section-aligned block computes.  Only the tests, the smoke check and the
+ * benchmark's cpu_baseline leg may call it; the GPU library shares no code,
+ * header, table or helper with this file.
+ *
+ * What each function follows:
+ *
+ *  fddo_block_attn      Block-causal attention (paper, Preliminaries,
+ *                       "Block-Causal Diffusion"): a block attends
+ *                       bidirectionally to itself and causally to the prompt
+ *                       and all earlier blocks, never to later ones.  With N
+ *                       rollouts forked from one KV cache (paper, "Shared
+ *                       prefix" paragraph of the test-time-scaling section)
+ *                       every rollout sees the same prefix rows and only its
+ *                       own block.  Written as the definition: scores over
+ *                       the L+B visible keys, max-subtracted two-pass softmax,
+ *                       weighted sum of the value rows.  No tiling, no
+ *                       streaming softmax, no reordering.
+ *
+ *  fddo_unmask_step     One iteration of "iteratively unmasks value
+ *                       positions" (paper, "Section Diffusion (SD)") under the
+ *                       masked-diffusion rule that visible tokens stay fixed
+ *                       (paper, "Masked Diffusion Language Models") and that
+ *                       diffusion acts on the editable set only, scaffold
+ *                       positions being frozen (paper, Eq. 2 and the scaffold
+ *                       construction paragraph).  The paper does not print
+ *                       the commit rule; the rule used is the task's:
+ *                       confidence = largest softmax probability, commit when
+ *                       it reaches tau, lowest index wins ties, and a block
+ *                       that has an eligible position commits at least one.
+ *
+ *  fddo_block_kv_update Synthetic stand-in for recomputing the K/V rows of
+ *                       positions that were just committed (no model is in
+ *                       scope): row (token mod T) of a table.
+ *
+ *  fddo_fork_block      "fork the KV cache N times": the private block state
+ *                       of one rollout replicated N times; the prefix is not
+ *                       touched (it is shared by reference).
+ *
+ * Pins (tests/test_oracle_*.py): brute-force explicit-mask attention,
+ * textbook causal attention for B=1, a library softmax-attention with an
+ * explicit mask, closed forms, logsumexp from scipy, and the invariants of
+ * the unmask rule.  fddo_block_kv_update and fddo_fork_block are pure copies
+ * and are pinned by direct comparison with numpy indexing.
+ *
+ * Element types: 0 = double, 1 = float, 2 = bfloat16 stored as uint16.
+ * Stored values are widened exactly to double before any arithmetic.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+static double widen(const void *p, int dtype, size_t i)
+{
+    if (dtype == 0) return ((const double *)p)[i];
+    if (dtype == 1) return (double)((const float *)p)[i];
+    uint32_t u = (uint32_t)((const uint16_t *)p)[i] << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+static size_t elem_size(int dtype) { return dtype == 0 ? 8 : dtype == 1 ? 4 : 2; }
+
+/*
+ * out = softmax(scale * q K_n^T) V_n with K_n = [prefix_k ; block_k[n]] for
+ * the KV head h / (Hq/Hkv).  rows == NULL: all (n,b,h), out is [N,B,Hq,D].
+ * rows != NULL: n_rows triples (n,b,h); out is [n_rows,D].
+ */
+int fddo_block_attn(int N, int B, int L, int Hq, int Hkv, int D, int dtype, double scale,
+                    const void *q, const void *prefix_k, const void *prefix_v,
+                    const void *block_k, const void *block_v,
+                    const int32_t *rows, int64_t n_rows, double *out)
+{
+    if (N <= 0 || B <= 0 || L < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv) return 1;
+    const int G = Hq / Hkv;
+    const int S = L + B;
+    const int64_t total = rows ? n_rows : (int64_t)N * B * Hq;
+    int bad = 0;
+#pragma omp parallel
+    {
+        double *s = (double *)malloc(sizeof(double) * (size_t)S);
+#pragma omp for schedule(dynamic, 4)
+        for (int64_t r = 0; r < total; ++r) {
+            int n, b, h;
+            if (rows) { n = rows[3 * r]; b = rows[3 * r + 1]; h = rows[3 * r + 2]; }
+            else { h = (int)(r % Hq); b = (int)((r / Hq) % B); n = (int)(r / ((int64_t)Hq * B)); }
+            if (n < 0 || n >= N || b < 0 || b >= B || h < 0 || h >= Hq) { bad = 1; continue; }
+            const int kh = h / G;
+            const size_t qo = (((size_t)n * B + b) * Hq + h) * D;
+            /* scores over every visible key: the prefix, then the own block */
+            double smax = -INFINITY;
+            for (int j = 0; j < S; ++j) {
+                double acc = 0.0;
+                if (j < L) {
+                    const size_t ko = ((size_t)j * Hkv + kh) * D;
+                    for (int d = 0; d < D; ++d) acc += widen(q, dtype, qo + d) * widen(prefix_k, dtype, ko + d);
+                } else {
+                    const size_t ko = (((size_t)n * B + (j - L)) * Hkv + kh) * D;
+                    for (int d = 0; d < D; ++d) acc += widen(q, dtype, qo + d) * widen(block_k, dtype, ko + d);
+                }
+                s[j] = scale * acc;
+                if (s[j] > smax) smax = s[j];
+            }
+            double z = 0.0;
+            for (int j = 0; j < S; ++j) { s[j] = exp(s[j] - smax); z += s[j]; }
+            double *o = out + (size_t)r * D;
+            for (int d = 0; d < D; ++d) o[d] = 0.0;
+            for (int j = 0; j < S; ++j) {
+                const double p = s[j] / z;
+                if (j < L) {
+                    const size_t vo = ((size_t)j * Hkv + kh) * D;
+                    for (int d = 0; d < D; ++d) o[d] += p * widen(prefix_v, dtype, vo + d);
+                } else {
+                    const size_t vo = (((size_t)n * B + (j - L)) * Hkv + kh) * D;
+                    for (int d = 0; d < D; ++d) o[d] += p * widen(block_v, dtype, vo + d);
+                }
+            }
+        }
+        free(s);
+    }
+    return bad;
+}
+
+/*
+ * One unmask iteration over N blocks.  mask and tokens are updated in place.
+ *   conf[n,b]      confidence of eligible positions, -inf elsewhere
+ *   cand[n,b]      argmax token of eligible positions, -1 elsewhere (may be NULL)
+ *   n_unmasked[n]  number of positions committed in block n (may be NULL)
+ *   committed[n,b] 1 where this call committed the position (may be NULL)
+ */
+int fddo_unmask_step(int N, int B, int64_t V, int dtype, double tau, const void *logits,
+                     const uint8_t *scaffold, uint8_t *mask, int32_t *tokens,
+                     double *conf, int32_t *cand, int32_t *n_unmasked, uint8_t *committed)
+{
+    if (N <= 0 || B <= 0 || V <= 0) return 1;
+    const int64_t NB = (int64_t)N * B;
+    int32_t *tok = (int32_t *)malloc(sizeof(int32_t) * (size_t)NB);
+    /* step 1-2: per eligible position, the arg max of the raw logits (lowest
+       id on ties) and the largest softmax probability 1 / sum exp(x - max) */
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t i = 0; i < NB; ++i) {
+        const int eligible = mask[i] == 1 && !(scaffold && scaffold[i]);
+        conf[i] = -INFINITY;
+        tok[i] = -1;
+        if (!eligible) continue;
+        const size_t base = (size_t)i * (size_t)V;
+        double xmax = widen(logits, dtype, base);
+        int64_t arg = 0;
+        for (int64_t v = 1; v < V; ++v) {
+            const double x = widen(logits, dtype, base + v);
+            if (x > xmax) { xmax = x; arg = v; }
+        }
+        double z = 0.0;
+        for (int64_t v = 0; v < V; ++v) z += exp(widen(logits, dtype, base + v) - xmax);
+        conf[i] = 1.0 / z;
+        tok[i] = (int32_t)arg;
+    }
+    /* step 3-6: per block, threshold test, forced single commit, write-back */
+    for (int n = 0; n < N; ++n) {
+        int count = 0, best = -1;
+        for (int b = 0; b < B; ++b) {
+            const int64_t i = (int64_t)n * B + b;
+            if (committed) committed[i] = 0;
+            if (tok[i] < 0) continue;                       /* not eligible */
+            if (best < 0 || conf[i] > conf[(int64_t)n * B + best]) best = b;
+            if (conf[i] >= tau) {
+                tokens[i] = tok[i]; mask[i] = 0; ++count;
+                if (committed) committed[i] = 1;
+            }
+        }
+        if (count == 0 && best >= 0) {
+            const int64_t i = (int64_t)n * B + best;
+            tokens[i] = tok[i]; mask[i] = 0; count = 1;
+            if (committed) committed[i] = 1;
+        }
+        if (n_unmasked) n_unmasked[n] = count;
+    }
+    if (cand) memcpy(cand, tok, sizeof(int32_t) * (size_t)NB);
+    free(tok);
+    return 0;
+}
+
+/* K/V rows of just-committed positions <- table row (token mod T). */
+int fddo_block_kv_update(int N, int B, int Hkv, int D, int T, int dtype,
+                         const int32_t *tokens, const uint8_t *committed,
+                         const void *table_k, const void *table_v,
+                         void *block_k, void *block_v)
+{
+    if (N <= 0 || B <= 0 || Hkv <= 0 || D <= 0 || T <= 0) return 1;
+    const size_t row = (size_t)Hkv * D * elem_size(dtype);
+    for (int64_t i = 0; i < (int64_t)N * B; ++i) {
+        if (!committed[i]) continue;
+        int64_t t = tokens[i] % T;
+        if (t < 0) t += T;
+        memcpy((char *)block_k + (size_t)i * row, (const char *)table_k + (size_t)t * row, row);
+        memcpy((char *)block_v + (size_t)i * row, (const char *)table_v + (size_t)t * row, row);
+    }
+    return 0;
+}
+
+/* dst[n] = src for n in [0,N): the private per-rollout state after a fork. */
+int fddo_fork_block(int N, size_t bytes, const void *src, void *dst)
+{
+    if (N <= 0) return 1;
+    for (int n = 0; n < N; ++n) memcpy((char *)dst + (size_t)n * bytes, src, bytes);
+    return 0;
+}
