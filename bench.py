@@ -1,0 +1,271 @@
+#!/usr/bin/env python3
+"""Benchmark of the denoise step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5]
+
+A "step" is one pass of the whole hot path over one batch of synthetic
+input that is already resident in HBM: shared-prefix block attention,
+confidence-threshold unmask over the vocabulary, and the K/V refresh of the
+committed positions; every 8 steps the N rollouts are re-forked from one
+parent block state (a new block starts), which is the fork bookkeeping.
+The default workload is the long multi-camera configuration (N=16 rollouts,
+B=64, prefix L=16384, V=152064, bf16).
+
+Prints ONE JSON line: whole-step throughput in rollout-tokens/s (N*B block
+positions per step, scaffold included), the roofline of the dominant kernel
+(attention on the matrix cores) from HIP events recorded around that kernel
+inside the timed region, the HBM roofline of the vocabulary reduction, the
+N=1 prefix-stream figures, and the fp64 CPU oracle timed on a bounded
+sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# Published MI355X peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_BF16_TFLOPS = 2500.0
+STEPS_PER_BLOCK = 8
+
+
+def dev(a):
+    import torch
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def attn_flops(w):
+    return 4.0 * w.N * w.B * w.Hq * (w.L + w.B) * w.D
+
+
+def attn_bytes(w, es=2):
+    prefix = 2 * w.L * w.Hkv * w.D * es
+    block = 2 * w.N * w.B * w.Hkv * w.D * es
+    qo = 2 * w.N * w.B * w.Hq * w.D * es
+    return prefix, prefix + block + qo
+
+
+class Events:
+    """Pairs of timing events, created and recorded once so their handles exist."""
+
+    def __init__(self, n):
+        import torch
+        self.pairs = []
+        for _ in range(n):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            b.record()
+            self.pairs.append((a, b))
+        torch.cuda.synchronize()
+
+    def mean_ms(self, used):
+        return float(np.mean([a.elapsed_time(b) for a, b in self.pairs[:used]]))
+
+
+def time_attention_only(F, w, steps, warmup, n_buffers):
+    """Attention alone on `n_buffers` distinct prefix buffers used in rotation
+    (cold caches when their total size exceeds the 256 MB last-level cache)."""
+    import torch
+    import fdd_workloads as W
+    d = W.attention_inputs(w)
+    q, bk, bv = dev(d["q"]), dev(d["block_k"]), dev(d["block_v"])
+    pk0, pv0 = dev(d["prefix_k"]), dev(d["prefix_v"])
+    pks = [pk0] + [pk0.clone() for _ in range(n_buffers - 1)]
+    pvs = [pv0] + [pv0.clone() for _ in range(n_buffers - 1)]
+    out = torch.empty_like(q)
+    ws_bytes = F.fdd_block_attn_workspace(q, pk0, pv0, bk, bv)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    ev = Events(steps)
+    for i in range(warmup):
+        F.fdd_block_attn(q, pks[i % n_buffers], pvs[i % n_buffers], bk, bv, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for i in range(steps):
+        F.fdd_profile_attn_events(*ev.pairs[i])
+        F.fdd_block_attn(q, pks[i % n_buffers], pvs[i % n_buffers], bk, bv, out=out, workspace=ws)
+    t1.record()
+    torch.cuda.synchronize()
+    F.fdd_profile_attn_events(None, None)
+    call_ms = t0.elapsed_time(t1) / steps
+    kern_ms = ev.mean_ms(steps)
+    prefix, total = attn_bytes(w)
+    return {
+        "workload": f"N={w.N} B={w.B} L={w.L} Hq={w.Hq} Hkv={w.Hkv} D={w.D} bf16, {n_buffers} rotating prefix buffers",
+        "call_us": round(call_ms * 1e3, 2), "kernel_us": round(kern_ms * 1e3, 2),
+        "prefix_bytes": prefix, "prefix_GBs_kernel": round(prefix / (kern_ms * 1e-3) / 1e9, 1),
+        "prefix_GBs_call": round(prefix / (call_ms * 1e-3) / 1e9, 1),
+        "frac_peak_hbm_kernel": round(prefix / (kern_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "rollout_tokens_per_s": round(w.N * w.B / (call_ms * 1e-3), 1),
+        "tflops_kernel": round(attn_flops(w) / (kern_ms * 1e-3) / 1e12, 1),
+    }
+
+
+def cpu_baseline(w, d, logits):
+    """The fp64 oracle as it stands on a bounded sample of one step."""
+    import oracle
+    rows_all = w.N * w.B * w.Hq
+    stride = max(1, rows_all // 4096)
+    idx = np.arange(0, rows_all, stride)
+    rows = np.stack([idx // (w.B * w.Hq), (idx // w.Hq) % w.B, idx % w.Hq], 1).astype(np.int32)
+    t = time.perf_counter()
+    oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"], rows=rows)
+    t_attn = (time.perf_counter() - t) * (rows_all / len(idx))
+    t_un = 0.0
+    n_un = 0
+    if logits is not None:
+        n_un = min(w.N, 4)
+        t = time.perf_counter()
+        oracle.unmask_step(logits[:n_un], d["mask"][:n_un], d["scaffold_mask"][:n_un], d["tokens"][:n_un],
+                           float(np.float32(w.tau)))
+        t_un = (time.perf_counter() - t) * (w.N / n_un)
+    t_step = t_attn + t_un
+    return {
+        "value": round(w.N * w.B / t_step, 2), "unit": "rollout-tokens/s", "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"attention on {len(idx)} of {rows_all} output rows (every {stride}th) and unmask on {n_un} of "
+                  f"{w.N} blocks of one step, each scaled to the full step; est. {t_step:.1f} s per step",
+        "host_cpu_count": os.cpu_count(),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-supplements", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
+
+    import torch
+    import fdd_workloads as W
+    import paper_2605_23163_amd as F
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    F.load_library()
+    torch.cuda.set_device(0)
+
+    w = W.CONFIGS[args.workload]
+    d = W.full_step_inputs(w, n_logit_steps=2)
+    g = {k: dev(d[k]) for k in ("q", "prefix_k", "prefix_v")}
+    scaffold = dev(d["scaffold_mask"])
+    has_unmask = w.V > 0
+    logits_h = None
+    if has_unmask:
+        # two distinct logits buffers in rotation (> 256 MB together at the default workload)
+        lrng = [np.random.default_rng([w.seed, 1000 + s]) for s in range(2)]
+        logits_h = W.step_logits(w, d["mask"], lrng[0])
+        logits = [dev(logits_h), dev(W.step_logits(w, d["mask"], lrng[1]))]
+        tk, tv = dev(d["table_k"]), dev(d["table_v"])
+    # parent block state the rollouts are forked from at the start of every block
+    parent = {k: dev(d[k][0]) for k in ("block_k", "block_v", "tokens", "mask")}
+    st = {k: torch.empty((w.N,) + tuple(parent[k].shape), dtype=parent[k].dtype, device="cuda") for k in parent}
+    out = torch.empty_like(g["q"])
+    conf = torch.empty((w.N, w.B), dtype=torch.float32, device="cuda")
+    nun = torch.empty((w.N,), dtype=torch.int32, device="cuda")
+    com = torch.empty((w.N, w.B), dtype=torch.uint8, device="cuda")
+    ws_a = torch.empty(max(256, F.fdd_block_attn_workspace(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"],
+                                                           st["block_v"])), dtype=torch.uint8, device="cuda")
+    ws_u = torch.empty(max(256, F.fdd_unmask_workspace(logits[0]) if has_unmask else 256), dtype=torch.uint8,
+                       device="cuda")
+    tau = float(np.float32(w.tau))
+
+    ev = Events(args.steps)
+    un0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    un1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+
+    def step(i, timed):
+        if timed:
+            F.fdd_profile_attn_events(*ev.pairs[i])
+        if i % STEPS_PER_BLOCK == 0:
+            for k in parent:
+                F.fdd_fork_block(parent[k], w.N, dst=st[k])
+        F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"], scaffold, out=out,
+                         workspace=ws_a)
+        if has_unmask:
+            if timed:
+                un0[i].record()
+            F.fdd_unmask_step(logits[i % 2], st["mask"], scaffold, tau, st["tokens"], conf, nun, com, workspace=ws_u)
+            if timed:
+                un1[i].record()
+            F.fdd_block_kv_update(st["tokens"], com, tk, tv, st["block_k"], st["block_v"])
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    wall0 = time.perf_counter()
+    t0.record()
+    for i in range(args.steps):
+        step(i, True)
+    t1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+    F.fdd_profile_attn_events(None, None)
+    ms_step = t0.elapsed_time(t1) / args.steps
+    attn_ms = ev.mean_ms(args.steps)
+    tokens_per_s = w.N * w.B / (ms_step * 1e-3)
+
+    flops = attn_flops(w)
+    res = {
+        "metric": "rollout-tokens/sec per denoise step", "value": round(tokens_per_s, 1), "unit": "rollout-tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: one denoise step (block attention + unmask + K/V refresh), N={w.N} "
+                               f"rollouts, B={w.B}, shared prefix L={w.L}, Hq={w.Hq}, Hkv={w.Hkv}, D={w.D}, V={w.V}, "
+                               f"bf16, re-forked every {STEPS_PER_BLOCK} steps",
+                   "N": w.N, "B": w.B, "L": w.L, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "V": w.V,
+                   "scaffold_frac": w.scaffold_frac, "tau": w.tau},
+        "wall_ms_per_step": round(wall * 1e3 / args.steps, 4),
+        "roofline": {"kernel": "attn_bf16_kernel", "bound": "mfma", "achieved": round(flops / (attn_ms * 1e-3) / 1e12, 2),
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "flops_per_launch": flops, "avg_launch_us": round(attn_ms * 1e3, 2)},
+    }
+    if has_unmask:
+        un_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(un0, un1)]))
+        # eligible rows shrink by the commits of each step; average over the steps of a block
+        elig0 = int(((d["mask"] == 1) & (d["scaffold_mask"] == 0)).sum())
+        st_host = st["mask"].cpu().numpy()
+        res["roofline_unmask"] = {
+            "kernel": "vocab_reduce_kernel+block_select_kernel", "bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS,
+            "avg_call_us": round(un_ms * 1e3, 2), "eligible_rows_at_block_start": elig0,
+            "eligible_rows_now": int(((st_host == 1) & (d["scaffold_mask"] == 0)).sum()),
+        }
+        # forced single commit per block per step at these logit statistics: rows = elig0 - N * (step in block)
+        avg_rows = elig0 - w.N * (STEPS_PER_BLOCK - 1) / 2.0
+        byt = avg_rows * w.V * 2
+        res["roofline_unmask"].update({"achieved": round(byt / (un_ms * 1e-3) / 1e9, 1),
+                                       "frac": round(byt / (un_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                       "bytes_per_call": byt})
+    if not args.no_supplements:
+        n1 = W.CONFIGS["cfg2"]
+        res["n1_prefix_stream"] = time_attention_only(F, n1, 400, 40, 128)
+        n1_long = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
+        res["n1_prefix_stream_L16384"] = time_attention_only(F, n1_long, 200, 20, 20)
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, d, logits_h)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,188 @@
+/*
+ * fdd.h -- C ABI of the MI355X (gfx950) block-diffusion denoise-step library.
+ *
+ * One denoising step of a section-aligned block, as the paper describes it:
+ *   - block-causal attention (Preliminaries, "Block-Causal Diffusion"): a
+ *     block attends bidirectionally to itself and causally to the prompt and
+ *     all earlier blocks, whose KV cache is reused without recomputation
+ *     ("Section Diffusion (SD)");
+ *   - N rollouts forked from one shared KV cache (test-time scaling section,
+ *     "Shared prefix"): every rollout owns a private block and they all read
+ *     the single prefix, which is never copied per rollout;
+ *   - confidence-threshold unmasking of still-masked value positions, with
+ *     the structural scaffold frozen (Eq. 2 and the scaffold construction
+ *     paragraph; "iteratively unmasks value positions").
+ *
+ * Conventions common to every call
+ *   - Every data pointer is a DEVICE pointer owned by the caller (HBM of the
+ *     current HIP device); the parameter structs themselves live on the host.
+ *     The library allocates no device memory, never copies the prefix and
+ *     never synchronises.  Work is enqueued on `stream` (a hipStream_t passed
+ *     as void*; NULL = the default stream) and the call returns at once.
+ *   - Arrays are dense, row-major, in the index order written next to them.
+ *   - The return code covers what the host can see: NULL pointers, shapes,
+ *     element type, workspace size, launch failure.  On error nothing is
+ *     launched and fdd_last_error() holds a message (thread-local).
+ *   - Inputs are never modified, except arrays documented as in/out.
+ *   - Scratch (`workspace`) must be at least what the matching
+ *     *_workspace() call returns for the same params, 256-byte aligned;
+ *     its contents before and after a call are unspecified.  Calls that
+ *     share a workspace must be ordered on one stream.
+ */
+#ifndef FDD_H
+#define FDD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FDD_OK = 0,
+    FDD_ERR_NULL = 1,        /* a required pointer is NULL */
+    FDD_ERR_SHAPE = 2,       /* non-positive size, Hq % Hkv != 0, ... */
+    FDD_ERR_DTYPE = 3,       /* element type not FDD_F32 / FDD_BF16 */
+    FDD_ERR_UNSUPPORTED = 4, /* head size or option outside the supported set */
+    FDD_ERR_WORKSPACE = 5,   /* workspace missing, misaligned or too small */
+    FDD_ERR_LAUNCH = 6       /* the HIP runtime refused a launch */
+} fdd_status;
+
+typedef enum { FDD_F32 = 0, FDD_BF16 = 1 } fdd_dtype;
+
+/* ------------------------------------------------------------------------
+ * fdd_block_attn: shared-prefix block-causal attention for N rollouts.
+ *
+ * For rollout n, block position b, query head h (KV head kh = h / (Hq/Hkv)):
+ *   keys   = prefix_k[0..L) ++ block_k[n, 0..B)      (head kh)
+ *   values = prefix_v[0..L) ++ block_v[n, 0..B)
+ *   out[n,b,h,:] = softmax(scale * q[n,b,h,:] . keys^T) values
+ * Every one of the L+B keys is visible (bidirectional inside the block,
+ * causal to the prefix); other rollouts' blocks are not.  This is the
+ * attention rule of "Block-Causal Diffusion" applied to rollouts that were
+ * forked from one cache ("Shared prefix").  Position encoding is outside
+ * this call: q and k arrive already rotated.
+ *
+ * scaffold_mask does not enter the arithmetic: scaffold tokens are ordinary
+ * visible tokens of the block (pre-filled, never masked), both as keys and
+ * as queries.  It is accepted so the signature matches the step's problem
+ * statement, may be NULL, and the output is the same for any value.
+ *
+ * dtype FDD_BF16: q/k/v/out are bfloat16, products on the matrix cores with
+ * fp32 accumulation, softmax in fp32.  dtype FDD_F32: fp32 storage and
+ * arithmetic.  D must be 64 or 128.  L may be 0.  `out` must not alias an
+ * input.  splits: number of pieces the prefix is cut into along L
+ * (0 = chosen by the library); the result does not depend on it beyond
+ * fp32 rounding.
+ */
+typedef struct fdd_attn_params {
+    int32_t N, B, L, Hq, Hkv, D;
+    int32_t dtype;                 /* fdd_dtype of q, k, v and out */
+    float scale;                   /* softmax scale; <= 0 selects 1/sqrt(D) */
+    const void *q;                 /* [N,B,Hq,D] */
+    const void *prefix_k;          /* [L,Hkv,D]  one copy for all rollouts; may be NULL iff L == 0 */
+    const void *prefix_v;          /* [L,Hkv,D] */
+    const void *block_k;           /* [N,B,Hkv,D] */
+    const void *block_v;           /* [N,B,Hkv,D] */
+    const uint8_t *scaffold_mask;  /* [N,B] 1 = frozen scaffold token; may be NULL */
+    void *out;                     /* [N,B,Hq,D] */
+    void *workspace;               /* >= fdd_block_attn_workspace() bytes */
+    size_t workspace_bytes;
+    void *stream;                  /* hipStream_t */
+    int32_t splits;                /* 0 = automatic */
+    int32_t reserved;              /* must be 0 */
+} fdd_attn_params;
+
+/* Bytes of scratch fdd_block_attn needs for these params (host-only
+ * arithmetic, no device is touched).  Returns 0 if the params are invalid. */
+size_t fdd_block_attn_workspace(const fdd_attn_params *p);
+fdd_status fdd_block_attn(const fdd_attn_params *p);
+
+/* ------------------------------------------------------------------------
+ * fdd_unmask_step: one confidence-threshold unmask iteration over N blocks.
+ *
+ * A position (n,b) is eligible when mask[n,b] == 1 and scaffold_mask[n,b]
+ * == 0: diffusion acts on the editable set only and visible tokens stay
+ * fixed (paper, Eq. 2; "Masked Diffusion Language Models").  For every
+ * eligible position
+ *     cand = lowest id attaining max_v logits[n,b,v]
+ *     conf = 1 / sum_v exp(logits[n,b,v] - max)      (largest softmax prob.)
+ * Block n commits every eligible position with conf >= tau; if none reaches
+ * tau and the block has an eligible position, it commits the eligible
+ * position of highest conf (lowest b on ties), so each call makes progress.
+ * Committing writes tokens[n,b] = cand and clears mask[n,b].  All other
+ * positions of tokens and mask are left as they were; a mask bit set on a
+ * scaffold position is ignored (the scaffold wins).
+ *
+ * Only the logits rows of eligible positions are read.  The arg max is taken
+ * on the stored logits (exact); exp and the sum run in fp32.
+ */
+typedef struct fdd_unmask_params {
+    int32_t N, B;
+    int64_t V;
+    int32_t dtype;                 /* fdd_dtype of logits */
+    float tau;
+    const void *logits;            /* [N,B,V] */
+    const uint8_t *scaffold_mask;  /* [N,B]; may be NULL (= no scaffold) */
+    uint8_t *mask;                 /* [N,B] in/out, 1 = still masked */
+    int32_t *tokens;               /* [N,B] in/out */
+    float *confidences;            /* [N,B] out: conf of eligible positions, -inf elsewhere */
+    int32_t *n_unmasked;           /* [N] out, commits per block; may be NULL */
+    uint8_t *committed;            /* [N,B] out, 1 = committed by this call; may be NULL */
+    void *workspace;               /* >= fdd_unmask_workspace() bytes */
+    size_t workspace_bytes;
+    void *stream;
+} fdd_unmask_params;
+
+size_t fdd_unmask_workspace(const fdd_unmask_params *p);
+fdd_status fdd_unmask_step(const fdd_unmask_params *p);
+
+/* ------------------------------------------------------------------------
+ * Rollout-fork bookkeeping ("fork the KV cache N times").
+ *
+ * fdd_fork_block: dst[n] = src for n in [0,N), `bytes` bytes each: the
+ * private per-rollout state (block K/V, tokens, mask) of the forked
+ * rollouts.  The prefix is shared by pointer and is not an argument.
+ * bytes must be a multiple of 4; src and dst must not overlap.
+ */
+fdd_status fdd_fork_block(int32_t N, size_t bytes, const void *src, void *dst, void *stream);
+
+/* fdd_block_kv_update: refresh the K/V rows of positions committed by the
+ * last unmask step.  No model is inside this library, so the new row of a
+ * position holding token t is row (t mod T) of caller-provided tables: a
+ * stand-in for embedding + projection.  Rows of other positions are not
+ * touched. */
+typedef struct fdd_kv_update_params {
+    int32_t N, B, Hkv, D, T;
+    int32_t dtype;                 /* fdd_dtype of the tables and the block K/V */
+    const int32_t *tokens;         /* [N,B] */
+    const uint8_t *committed;      /* [N,B] as written by fdd_unmask_step */
+    const void *table_k;           /* [T,Hkv,D] */
+    const void *table_v;           /* [T,Hkv,D] */
+    void *block_k;                 /* [N,B,Hkv,D] in/out */
+    void *block_v;                 /* [N,B,Hkv,D] in/out */
+    void *stream;
+} fdd_kv_update_params;
+
+fdd_status fdd_block_kv_update(const fdd_kv_update_params *p);
+
+/* ------------------------------------------------------------------------
+ * Timing hook for benchmarks.  While set (both non-NULL), every
+ * fdd_block_attn call made by this host thread records `start` on the call's
+ * stream right before the main attention kernel and `stop` right after it
+ * (before the small merge kernel), so hipEventElapsedTime(start, stop) is
+ * that kernel's duration.  Both are hipEvent_t passed as void*, owned by the
+ * caller.  Pass NULL, NULL to clear.  Not meant for production loops.
+ */
+fdd_status fdd_profile_attn_events(void *start, void *stop);
+
+/* Message of the last failing call on this thread ("" if none). */
+const char *fdd_last_error(void);
+/* major*10000 + minor*100 + patch */
+int fdd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDD_H */

@@ -49,6 +49,13 @@ def _load():
     return _lib
 
 
+def num_threads() -> int:
+    """Threads the oracle's parallel loops use (reported with CPU timings)."""
+    lib = _load()
+    lib.fddo_num_threads.restype = ctypes.c_int
+    return int(lib.fddo_num_threads())
+
+
 def _ptr(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 

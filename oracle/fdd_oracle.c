@@ -54,6 +54,20 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* number of threads the parallel loops below will use (for reporting only) */
+int fddo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 static double widen(const void *p, int dtype, size_t i)
 {
     if (dtype == 0) return ((const double *)p)[i];

@@ -1,0 +1,260 @@
+"""ctypes binding of the C ABI declared in ``include/fdd.h``.
+
+Argument marshalling only: tensors in, pointers and sizes out.  Every step of
+the path runs inside the library's HIP kernels; there is no fallback.  torch
+is used for device memory and for the current stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfdd.so")
+_lib = None
+
+FDD_F32, FDD_BF16 = 0, 1
+EXPORTS = ("fdd_block_attn_workspace", "fdd_block_attn", "fdd_unmask_workspace", "fdd_unmask_step",
+           "fdd_fork_block", "fdd_block_kv_update", "fdd_profile_attn_events", "fdd_last_error", "fdd_version")
+
+
+class FddError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"fdd status {code}: {msg}")
+        self.code = code
+
+
+class AttnParams(C.Structure):
+    _fields_ = [("N", C.c_int32), ("B", C.c_int32), ("L", C.c_int32), ("Hq", C.c_int32), ("Hkv", C.c_int32),
+                ("D", C.c_int32), ("dtype", C.c_int32), ("scale", C.c_float),
+                ("q", C.c_void_p), ("prefix_k", C.c_void_p), ("prefix_v", C.c_void_p),
+                ("block_k", C.c_void_p), ("block_v", C.c_void_p), ("scaffold_mask", C.c_void_p),
+                ("out", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("stream", C.c_void_p), ("splits", C.c_int32), ("reserved", C.c_int32)]
+
+
+class UnmaskParams(C.Structure):
+    _fields_ = [("N", C.c_int32), ("B", C.c_int32), ("V", C.c_int64), ("dtype", C.c_int32), ("tau", C.c_float),
+                ("logits", C.c_void_p), ("scaffold_mask", C.c_void_p), ("mask", C.c_void_p),
+                ("tokens", C.c_void_p), ("confidences", C.c_void_p), ("n_unmasked", C.c_void_p),
+                ("committed", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("stream", C.c_void_p)]
+
+
+class KvUpdateParams(C.Structure):
+    _fields_ = [("N", C.c_int32), ("B", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32), ("T", C.c_int32),
+                ("dtype", C.c_int32), ("tokens", C.c_void_p), ("committed", C.c_void_p),
+                ("table_k", C.c_void_p), ("table_v", C.c_void_p), ("block_k", C.c_void_p),
+                ("block_v", C.c_void_p), ("stream", C.c_void_p)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libfdd.so (after torch, so both share one HIP runtime)."""
+    global _lib
+    if _lib is None:
+        import torch  # noqa: F401  -- brings in the HIP runtime the library links against
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2605_23163_amd.build` "
+                "(there is no fallback path)")
+        lib = C.CDLL(_LIB_PATH)
+        lib.fdd_block_attn_workspace.restype = C.c_size_t
+        lib.fdd_block_attn_workspace.argtypes = [C.POINTER(AttnParams)]
+        lib.fdd_block_attn.restype = C.c_int
+        lib.fdd_block_attn.argtypes = [C.POINTER(AttnParams)]
+        lib.fdd_unmask_workspace.restype = C.c_size_t
+        lib.fdd_unmask_workspace.argtypes = [C.POINTER(UnmaskParams)]
+        lib.fdd_unmask_step.restype = C.c_int
+        lib.fdd_unmask_step.argtypes = [C.POINTER(UnmaskParams)]
+        lib.fdd_fork_block.restype = C.c_int
+        lib.fdd_fork_block.argtypes = [C.c_int32, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
+        lib.fdd_block_kv_update.restype = C.c_int
+        lib.fdd_block_kv_update.argtypes = [C.POINTER(KvUpdateParams)]
+        lib.fdd_profile_attn_events.restype = C.c_int
+        lib.fdd_profile_attn_events.argtypes = [C.c_void_p, C.c_void_p]
+        lib.fdd_last_error.restype = C.c_char_p
+        lib.fdd_version.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def fdd_last_error() -> str:
+    return load_library().fdd_last_error().decode()
+
+
+def fdd_version() -> int:
+    return load_library().fdd_version()
+
+
+def fdd_profile_attn_events(start=None, stop=None):
+    """Record two torch.cuda.Event (created with enable_timing=True and already
+    recorded once, so that their handles exist) around the main attention
+    kernel of every following fdd_block_attn call; None, None clears."""
+    a = None if start is None else start.cuda_event
+    b = None if stop is None else stop.cuda_event
+    _check(load_library().fdd_profile_attn_events(a, b))
+
+
+def _check(code):
+    if code != 0:
+        raise FddError(code, fdd_last_error())
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return FDD_BF16
+    if t.dtype == torch.float32:
+        return FDD_F32
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _dev(t, name):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live in GPU memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def _workspace(ws, need, device):
+    import torch
+    if need == 0:
+        return None, 0
+    if ws is None:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+    return ws, ws.numel() * ws.element_size()
+
+
+def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits):
+    N, B, Hq, D = q.shape
+    L, Hkv = prefix_k.shape[0], block_k.shape[2]
+    if tuple(prefix_k.shape[1:]) != (Hkv, D) or tuple(prefix_v.shape) != tuple(prefix_k.shape):
+        raise ValueError("prefix_k / prefix_v must be [L,Hkv,D]")
+    if tuple(block_k.shape) != (N, B, Hkv, D) or tuple(block_v.shape) != (N, B, Hkv, D):
+        raise ValueError("block_k / block_v must be [N,B,Hkv,D]")
+    dt = _dtype_code(q)
+    for t in (prefix_k, prefix_v, block_k, block_v):
+        if t.dtype != q.dtype:
+            raise TypeError("q, k and v must share one element type")
+    p = AttnParams()
+    p.N, p.B, p.L, p.Hq, p.Hkv, p.D, p.dtype = N, B, L, Hq, Hkv, D, dt
+    p.scale = 0.0 if scale is None else float(scale)
+    p.q = _dev(q, "q")
+    p.prefix_k = _dev(prefix_k, "prefix_k") if L > 0 else None
+    p.prefix_v = _dev(prefix_v, "prefix_v") if L > 0 else None
+    p.block_k, p.block_v = _dev(block_k, "block_k"), _dev(block_v, "block_v")
+    p.scaffold_mask = _dev(scaffold_mask, "scaffold_mask")
+    p.out = _dev(out, "out") if out is not None else None
+    p.splits = int(splits)
+    return p
+
+
+def fdd_block_attn_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0) -> int:
+    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, None, None, None, splits)
+    return load_library().fdd_block_attn_workspace(C.byref(p))
+
+
+def fdd_block_attn(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask=None, out=None, scale=None,
+                   workspace=None, stream=None, splits=0):
+    """out[N,B,Hq,D] = shared-prefix block-causal attention (see include/fdd.h)."""
+    import torch
+    lib = load_library()
+    if out is None:
+        out = torch.empty_like(q)
+    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits)
+    need = lib.fdd_block_attn_workspace(C.byref(p))
+    ws, nbytes = _workspace(workspace, need, q.device)
+    p.workspace = ws.data_ptr() if ws is not None else None
+    p.workspace_bytes = nbytes
+    p.stream = _stream_ptr(stream)
+    _check(lib.fdd_block_attn(C.byref(p)))
+    return out
+
+
+def _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed):
+    N, B, V = logits.shape
+    p = UnmaskParams()
+    p.N, p.B, p.V, p.dtype, p.tau = N, B, V, _dtype_code(logits), float(tau)
+    p.logits = _dev(logits, "logits")
+    p.scaffold_mask = _dev(scaffold_mask, "scaffold_mask")
+    p.mask, p.tokens = _dev(mask, "mask"), _dev(tokens, "tokens")
+    p.confidences = _dev(confidences, "confidences")
+    p.n_unmasked = _dev(n_unmasked, "n_unmasked")
+    p.committed = _dev(committed, "committed")
+    return p
+
+
+def fdd_unmask_workspace(logits) -> int:
+    p = _unmask_params(logits, None, None, None, 0.0, None, None, None)
+    return load_library().fdd_unmask_workspace(C.byref(p))
+
+
+def fdd_unmask_step(logits, mask, scaffold_mask, tau, tokens, confidences=None, n_unmasked=None, committed=None,
+                    workspace=None, stream=None):
+    """One unmask iteration; ``tokens`` and ``mask`` are updated in place.
+
+    Returns (tokens, confidences, n_unmasked, committed).
+    """
+    import torch
+    lib = load_library()
+    N, B, V = logits.shape
+    for t, dt, nm in ((mask, torch.uint8, "mask"), (tokens, torch.int32, "tokens")):
+        if t.dtype != dt or tuple(t.shape) != (N, B):
+            raise TypeError(f"{nm} must be {dt} [N,B]")
+    if scaffold_mask is not None and (scaffold_mask.dtype != torch.uint8 or tuple(scaffold_mask.shape) != (N, B)):
+        raise TypeError("scaffold_mask must be uint8 [N,B]")
+    dev = logits.device
+    if confidences is None:
+        confidences = torch.empty((N, B), dtype=torch.float32, device=dev)
+    if n_unmasked is None:
+        n_unmasked = torch.empty((N,), dtype=torch.int32, device=dev)
+    if committed is None:
+        committed = torch.empty((N, B), dtype=torch.uint8, device=dev)
+    p = _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed)
+    need = lib.fdd_unmask_workspace(C.byref(p))
+    ws, nbytes = _workspace(workspace, need, dev)
+    p.workspace = ws.data_ptr() if ws is not None else None
+    p.workspace_bytes = nbytes
+    p.stream = _stream_ptr(stream)
+    _check(lib.fdd_unmask_step(C.byref(p)))
+    return tokens, confidences, n_unmasked, committed
+
+
+def fdd_fork_block(src, N, dst=None, stream=None):
+    """dst[n] = src for n < N: the private block state of N forked rollouts."""
+    import torch
+    lib = load_library()
+    if dst is None:
+        dst = torch.empty((N,) + tuple(src.shape), dtype=src.dtype, device=src.device)
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != N * nbytes:
+        raise ValueError("dst must hold N copies of src")
+    _check(lib.fdd_fork_block(N, nbytes, _dev(src, "src"), _dev(dst, "dst"), _stream_ptr(stream)))
+    return dst
+
+
+def fdd_block_kv_update(tokens, committed, table_k, table_v, block_k, block_v, stream=None):
+    """Refresh block_k / block_v rows of committed positions in place."""
+    lib = load_library()
+    N, B, Hkv, D = block_k.shape
+    p = KvUpdateParams()
+    p.N, p.B, p.Hkv, p.D, p.T, p.dtype = N, B, Hkv, D, table_k.shape[0], _dtype_code(block_k)
+    p.tokens, p.committed = _dev(tokens, "tokens"), _dev(committed, "committed")
+    p.table_k, p.table_v = _dev(table_k, "table_k"), _dev(table_v, "table_v")
+    p.block_k, p.block_v = _dev(block_k, "block_k"), _dev(block_v, "block_v")
+    p.stream = _stream_ptr(stream)
+    _check(lib.fdd_block_kv_update(C.byref(p)))
+    return block_k, block_v

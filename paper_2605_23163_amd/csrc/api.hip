@@ -1,0 +1,206 @@
+// C ABI entry points: host-side validation, planning and launches.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+
+#include "fdd_internal.h"
+
+namespace fdd {
+namespace {
+
+thread_local char g_err[256] = "";
+thread_local hipEvent_t g_ev_start = nullptr;
+thread_local hipEvent_t g_ev_stop = nullptr;
+
+fdd_status fail(fdd_status code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+fdd_status check_attn_shape(const fdd_attn_params* p)
+{
+    if (!p) return fail(FDD_ERR_NULL, "fdd_block_attn: params is NULL");
+    if (p->N <= 0 || p->B <= 0 || p->L < 0 || p->Hq <= 0 || p->Hkv <= 0 || p->D <= 0)
+        return fail(FDD_ERR_SHAPE, "fdd_block_attn: N, B, Hq, Hkv, D must be positive and L >= 0 (got N=%d B=%d L=%d Hq=%d Hkv=%d D=%d)",
+                    p->N, p->B, p->L, p->Hq, p->Hkv, p->D);
+    if (p->Hq % p->Hkv) return fail(FDD_ERR_SHAPE, "fdd_block_attn: Hq=%d is not a multiple of Hkv=%d", p->Hq, p->Hkv);
+    if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_block_attn: dtype %d is neither FDD_F32 nor FDD_BF16", p->dtype);
+    if (p->D != 64 && p->D != 128) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: head size D=%d not supported (64 or 128)", p->D);
+    if (p->splits < 0 || p->splits > 64) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: splits=%d outside [0, 64]", p->splits);
+    if (p->reserved != 0) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: reserved field must be 0");
+    if ((long long)p->N * p->B * (p->Hq / p->Hkv) > (1ll << 30) || (long long)p->N * p->B * p->Hq * p->D > (1ll << 40))
+        return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq too large");
+    if (std::isnan(p->scale) || std::isinf(p->scale)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: scale is not finite");
+    return FDD_OK;
+}
+
+}  // namespace
+
+bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
+{
+    AttnPlan pl;
+    pl.G = p.Hq / p.Hkv;
+    pl.R = p.N * p.B * pl.G;
+    if (p.dtype == FDD_BF16) {
+        pl.mtile_rows = 256;
+        pl.key_tile = 64;
+    } else {
+        pl.mtile_rows = 16;
+        pl.key_tile = 32;
+    }
+    pl.MT = (pl.R + pl.mtile_rows - 1) / pl.mtile_rows;
+    pl.TP = (p.L + pl.key_tile - 1) / pl.key_tile;
+    int s = p.splits;
+    if (s == 0) {
+        // one workgroup per compute unit when the M-tiles alone cannot fill the chip
+        const long long base = (long long)p.Hkv * pl.MT;
+        s = (int)(kNumCU / base);
+        if (s > 64) s = 64;
+    }
+    if (s > pl.TP) s = pl.TP;
+    if (s < 1) s = 1;
+    pl.splits = s;
+    if (s > 1) {
+        const size_t prow = (size_t)p.Hkv * pl.MT * s * pl.mtile_rows;
+        pl.ws_o_bytes = (prow * p.D * sizeof(float) + 255) & ~(size_t)255;
+        pl.ws_ml_bytes = (prow * 2 * sizeof(float) + 255) & ~(size_t)255;
+    } else {
+        pl.ws_o_bytes = 0;
+        pl.ws_ml_bytes = 0;
+    }
+    *plan = pl;
+    return true;
+}
+
+}  // namespace fdd
+
+using namespace fdd;
+
+extern "C" {
+
+size_t fdd_block_attn_workspace(const fdd_attn_params* p)
+{
+    if (check_attn_shape(p) != FDD_OK) return 0;
+    AttnPlan plan;
+    make_attn_plan(*p, &plan);
+    return plan.ws_o_bytes + plan.ws_ml_bytes;
+}
+
+fdd_status fdd_block_attn(const fdd_attn_params* p)
+{
+    fdd_status st = check_attn_shape(p);
+    if (st != FDD_OK) return st;
+    if (!p->q || !p->block_k || !p->block_v || !p->out) return fail(FDD_ERR_NULL, "fdd_block_attn: q, block_k, block_v and out must not be NULL");
+    if (p->L > 0 && (!p->prefix_k || !p->prefix_v)) return fail(FDD_ERR_NULL, "fdd_block_attn: prefix_k / prefix_v is NULL with L=%d", p->L);
+    const void* ptrs[] = {p->q, p->prefix_k, p->prefix_v, p->block_k, p->block_v, p->out};
+    for (const void* x : ptrs)
+        if (x && !aligned16(x)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: data pointers must be 16-byte aligned");
+    if (p->out == p->q) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: out must not alias q");
+    AttnPlan plan;
+    make_attn_plan(*p, &plan);
+    const size_t need = plan.ws_o_bytes + plan.ws_ml_bytes;
+    if (need > 0) {
+        if (!p->workspace) return fail(FDD_ERR_WORKSPACE, "fdd_block_attn: workspace is NULL, %zu bytes needed", need);
+        if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return fail(FDD_ERR_WORKSPACE, "fdd_block_attn: workspace must be 256-byte aligned");
+        if (p->workspace_bytes < need) return fail(FDD_ERR_WORKSPACE, "fdd_block_attn: workspace has %zu bytes, %zu needed", p->workspace_bytes, need);
+    }
+    const float scale = p->scale > 0.f ? p->scale : 1.f / std::sqrt((float)p->D);
+    hipStream_t s = static_cast<hipStream_t>(p->stream);
+    const bool timed = g_ev_start && g_ev_stop;
+    if (timed && hipEventRecord(g_ev_start, s) != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: cannot record the start event");
+    hipError_t e = (p->dtype == FDD_BF16) ? launch_attn_bf16(*p, plan, scale, s) : launch_attn_f32(*p, plan, scale, s);
+    if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: launch failed: %s", hipGetErrorString(e));
+    if (timed && hipEventRecord(g_ev_stop, s) != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: cannot record the stop event");
+    if (plan.splits > 1) {
+        e = launch_attn_combine(*p, plan, scale, s);
+        if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: merge launch failed: %s", hipGetErrorString(e));
+    }
+    return FDD_OK;
+}
+
+static fdd_status check_unmask_shape(const fdd_unmask_params* p)
+{
+    if (!p) return fail(FDD_ERR_NULL, "fdd_unmask_step: params is NULL");
+    if (p->N <= 0 || p->B <= 0 || p->V <= 0) return fail(FDD_ERR_SHAPE, "fdd_unmask_step: N, B, V must be positive (got N=%d B=%d V=%lld)", p->N, p->B, (long long)p->V);
+    if (p->V >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_unmask_step: V must be below 2^31");
+    if ((long long)p->N * p->B > (1ll << 24)) return fail(FDD_ERR_SHAPE, "fdd_unmask_step: N*B too large");
+    if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_unmask_step: dtype %d is neither FDD_F32 nor FDD_BF16", p->dtype);
+    if (std::isnan(p->tau)) return fail(FDD_ERR_UNSUPPORTED, "fdd_unmask_step: tau is NaN");
+    return FDD_OK;
+}
+
+size_t fdd_unmask_workspace(const fdd_unmask_params* p)
+{
+    if (check_unmask_shape(p) != FDD_OK) return 0;
+    UnmaskPlan plan;
+    make_unmask_plan(*p, &plan);
+    return plan.ws_bytes;
+}
+
+fdd_status fdd_unmask_step(const fdd_unmask_params* p)
+{
+    fdd_status st = check_unmask_shape(p);
+    if (st != FDD_OK) return st;
+    if (!p->logits || !p->mask || !p->tokens || !p->confidences)
+        return fail(FDD_ERR_NULL, "fdd_unmask_step: logits, mask, tokens and confidences must not be NULL");
+    if (!aligned16(p->logits)) return fail(FDD_ERR_UNSUPPORTED, "fdd_unmask_step: logits must be 16-byte aligned");
+    UnmaskPlan plan;
+    make_unmask_plan(*p, &plan);
+    if (!p->workspace) return fail(FDD_ERR_WORKSPACE, "fdd_unmask_step: workspace is NULL, %zu bytes needed", plan.ws_bytes);
+    if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return fail(FDD_ERR_WORKSPACE, "fdd_unmask_step: workspace must be 256-byte aligned");
+    if (p->workspace_bytes < plan.ws_bytes) return fail(FDD_ERR_WORKSPACE, "fdd_unmask_step: workspace has %zu bytes, %zu needed", p->workspace_bytes, plan.ws_bytes);
+    hipError_t e = launch_unmask(*p, plan, static_cast<hipStream_t>(p->stream));
+    if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_unmask_step: launch failed: %s", hipGetErrorString(e));
+    return FDD_OK;
+}
+
+fdd_status fdd_fork_block(int32_t N, size_t bytes, const void* src, void* dst, void* stream)
+{
+    if (!src || !dst) return fail(FDD_ERR_NULL, "fdd_fork_block: src and dst must not be NULL");
+    if (N <= 0 || bytes == 0) return fail(FDD_ERR_SHAPE, "fdd_fork_block: N and bytes must be positive");
+    if (bytes % 4 || (reinterpret_cast<uintptr_t>(src) & 3u) || (reinterpret_cast<uintptr_t>(dst) & 3u))
+        return fail(FDD_ERR_UNSUPPORTED, "fdd_fork_block: bytes and pointers must be multiples of 4");
+    const char* s0 = static_cast<const char*>(src);
+    const char* d0 = static_cast<const char*>(dst);
+    if (s0 < d0 + (size_t)N * bytes && d0 < s0 + bytes) return fail(FDD_ERR_UNSUPPORTED, "fdd_fork_block: src and dst overlap");
+    hipError_t e = launch_fork_block(N, bytes, src, dst, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_fork_block: launch failed: %s", hipGetErrorString(e));
+    return FDD_OK;
+}
+
+fdd_status fdd_block_kv_update(const fdd_kv_update_params* p)
+{
+    if (!p) return fail(FDD_ERR_NULL, "fdd_block_kv_update: params is NULL");
+    if (p->N <= 0 || p->B <= 0 || p->Hkv <= 0 || p->D <= 0 || p->T <= 0)
+        return fail(FDD_ERR_SHAPE, "fdd_block_kv_update: N, B, Hkv, D, T must be positive");
+    if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_block_kv_update: dtype %d is neither FDD_F32 nor FDD_BF16", p->dtype);
+    if (!p->tokens || !p->committed || !p->table_k || !p->table_v || !p->block_k || !p->block_v)
+        return fail(FDD_ERR_NULL, "fdd_block_kv_update: all pointers must be non-NULL");
+    const size_t es = p->dtype == FDD_BF16 ? 2 : 4;
+    if (((size_t)p->Hkv * p->D * es) % 16) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_kv_update: a K/V row (Hkv*D elements) must be a multiple of 16 bytes");
+    if (!aligned16(p->table_k) || !aligned16(p->table_v) || !aligned16(p->block_k) || !aligned16(p->block_v))
+        return fail(FDD_ERR_UNSUPPORTED, "fdd_block_kv_update: tables and block K/V must be 16-byte aligned");
+    hipError_t e = launch_kv_update(*p, static_cast<hipStream_t>(p->stream));
+    if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_kv_update: launch failed: %s", hipGetErrorString(e));
+    return FDD_OK;
+}
+
+fdd_status fdd_profile_attn_events(void* start, void* stop)
+{
+    if ((start == nullptr) != (stop == nullptr)) return fail(FDD_ERR_NULL, "fdd_profile_attn_events: pass two events or two NULLs");
+    g_ev_start = static_cast<hipEvent_t>(start);
+    g_ev_stop = static_cast<hipEvent_t>(stop);
+    return FDD_OK;
+}
+
+const char* fdd_last_error(void) { return g_err; }
+
+int fdd_version(void) { return 100; }
+
+}  // extern "C"

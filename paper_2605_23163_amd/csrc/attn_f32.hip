@@ -1,0 +1,272 @@
+// Shared-prefix block-causal attention, fp32 storage and arithmetic, and the
+// split merge used by both storage types.
+//
+// The fp32 path exists for exactness checks on small problems (the bf16
+// matrix-core kernel is the performance path).  It computes the same thing
+// (paper, "Block-Causal Diffusion" and "Shared prefix") with plain fp32 FMAs:
+// a workgroup owns 16 stacked query rows of one KV head and one piece of the
+// key range, stages 32-key K/V tiles in LDS, and keeps the streaming-softmax
+// state (m, l, o) per row.
+#include "fdd_internal.h"
+
+namespace fdd {
+namespace {
+
+constexpr int KT = 32;     // keys per tile
+constexpr int RT = 16;     // rows per workgroup
+constexpr int THREADS = 256;
+
+struct Args {
+    const float* q;
+    const float* pk;
+    const float* pv;
+    const float* bk;
+    const float* bv;
+    float* out;
+    float* ws_o;
+    float* ws_ml;
+    int N, B, L, Hq, Hkv, G, R, MT, TP, S;
+    float c;   // scale * log2(e)
+};
+
+template <int D>
+__global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
+{
+    constexpr int DP = D + 4;          // padded row length (floats), keeps float4 alignment
+    constexpr int DPT = D / 16;        // output channels per thread
+    __shared__ __align__(16) float qs[RT * DP];
+    __shared__ __align__(16) float ks[KT * DP];
+    __shared__ __align__(16) float vs[KT * DP];
+    __shared__ float ps[RT * (KT + 1)];
+
+    const int tid = threadIdx.x;
+    const int mt = blockIdx.x;
+    const int split = blockIdx.y;
+    const int kh = blockIdx.z;
+    const int BG = a.B * a.G;
+
+    const int r_loc = tid / 16;         // row of this thread inside the workgroup tile
+    const int sub = tid % 16;           // 16 threads cooperate on a row
+    const int row = mt * RT + r_loc;
+    const bool row_ok = row < a.R;
+    const int nb = row_ok ? row / a.G : 0;
+    const int g = row_ok ? row % a.G : 0;
+    const int my_rollout = row_ok ? nb / a.B : -1;
+    const int wg_row_hi = min(mt * RT + RT - 1, a.R - 1);
+    const int wg_n_lo = (mt * RT) / BG;
+    const int wg_n_hi = wg_row_hi / BG;
+
+    // stage the query rows
+    for (int i = tid; i < RT * (D / 4); i += THREADS) {
+        const int r = i / (D / 4), c4 = i % (D / 4);
+        const int rr = mt * RT + r;
+        float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (rr < a.R) {
+            const int nb_ = rr / a.G, g_ = rr % a.G;
+            x = *reinterpret_cast<const float4*>(a.q + ((size_t)nb_ * a.Hq + (size_t)kh * a.G + g_) * D + c4 * 4);
+        }
+        *reinterpret_cast<float4*>(&qs[r * DP + c4 * 4]) = x;
+    }
+
+    const int t0 = (int)(((long long)split * a.TP) / a.S);
+    const int t1 = (int)(((long long)(split + 1) * a.TP) / a.S);
+    const int n_prefix = t1 - t0;
+    const int tail_per = (a.B + KT - 1) / KT;
+    const int n_tail = (split == a.S - 1) ? (wg_n_hi - wg_n_lo + 1) * tail_per : 0;
+    const size_t kv_stride = (size_t)a.Hkv * D;
+
+    float o[DPT];
+#pragma unroll
+    for (int j = 0; j < DPT; ++j) o[j] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    for (int i = 0; i < n_prefix + n_tail; ++i) {
+        const float *kp, *vp;
+        int valid, rollout;
+        if (i < n_prefix) {
+            const int key0 = (t0 + i) * KT;
+            kp = a.pk + (size_t)key0 * kv_stride + (size_t)kh * D;
+            vp = a.pv + (size_t)key0 * kv_stride + (size_t)kh * D;
+            valid = min(KT, a.L - key0);
+            rollout = -1;
+        } else {
+            const int j = i - n_prefix;
+            const int n = wg_n_lo + j / tail_per;
+            const int key0 = (j % tail_per) * KT;
+            const size_t off = ((size_t)n * a.B + key0) * kv_stride + (size_t)kh * D;
+            kp = a.bk + off;
+            vp = a.bv + off;
+            valid = min(KT, a.B - key0);
+            rollout = n;
+        }
+        __syncthreads();   // previous tile fully consumed (and qs written, first time)
+        for (int x = tid; x < KT * (D / 4); x += THREADS) {
+            const int key = x / (D / 4), c4 = x % (D / 4);
+            float4 kk = make_float4(0.f, 0.f, 0.f, 0.f), vv = kk;
+            if (key < valid) {
+                kk = *reinterpret_cast<const float4*>(kp + (size_t)key * kv_stride + c4 * 4);
+                vv = *reinterpret_cast<const float4*>(vp + (size_t)key * kv_stride + c4 * 4);
+            }
+            *reinterpret_cast<float4*>(&ks[key * DP + c4 * 4]) = kk;
+            *reinterpret_cast<float4*>(&vs[key * DP + c4 * 4]) = vv;
+        }
+        __syncthreads();
+
+        // scores of KT/16 keys per thread: keys sub, sub+16, ...
+        const bool sees = rollout < 0 || rollout == my_rollout;
+        constexpr int KPT = KT / 16;
+        float sc[KPT];
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const int key = sub + 16 * j;
+            float acc = 0.f;
+            for (int d = 0; d < D; d += 4) {
+                const float4 qq = *reinterpret_cast<const float4*>(&qs[r_loc * DP + d]);
+                const float4 kk = *reinterpret_cast<const float4*>(&ks[key * DP + d]);
+                acc = fmaf(qq.x, kk.x, acc);
+                acc = fmaf(qq.y, kk.y, acc);
+                acc = fmaf(qq.z, kk.z, acc);
+                acc = fmaf(qq.w, kk.w, acc);
+            }
+            sc[j] = (sees && key < valid) ? acc : -INFINITY;
+            mx = fmaxf(mx, sc[j]);
+        }
+#pragma unroll
+        for (int w = 8; w >= 1; w >>= 1) mx = fmaxf(mx, __shfl_xor(mx, w, 16));
+        const float m_new = fmaxf(m_run, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = exp2f((m_run - m_use) * a.c);
+        float psum = 0.f;
+#pragma unroll
+        for (int j = 0; j < KPT; ++j) {
+            const float p = exp2f((sc[j] - m_use) * a.c);
+            psum += p;
+            ps[r_loc * (KT + 1) + sub + 16 * j] = p;
+        }
+#pragma unroll
+        for (int w = 8; w >= 1; w >>= 1) psum += __shfl_xor(psum, w, 16);
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        __syncthreads();   // ps visible to the 16 threads of the row
+#pragma unroll
+        for (int j = 0; j < DPT; ++j) o[j] *= alpha;
+        for (int key = 0; key < KT; ++key) {
+            const float p = ps[r_loc * (KT + 1) + key];
+#pragma unroll
+            for (int j = 0; j < DPT; ++j) o[j] = fmaf(p, vs[key * DP + sub * DPT + j], o[j]);
+        }
+    }
+
+    if (!row_ok) return;
+    if (a.S == 1) {
+        float* op = a.out + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D + sub * DPT;
+        const float inv = 1.f / l_run;
+#pragma unroll
+        for (int j = 0; j < DPT; ++j) op[j] = o[j] * inv;
+    } else {
+        const size_t prow = (((size_t)kh * a.MT + mt) * a.S + split) * RT + r_loc;
+        float* wo = a.ws_o + prow * D + sub * DPT;
+#pragma unroll
+        for (int j = 0; j < DPT; ++j) wo[j] = o[j];
+        if (sub == 0) {
+            a.ws_ml[prow * 2 + 0] = m_run;
+            a.ws_ml[prow * 2 + 1] = l_run;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Merge of the per-split partials (log-sum-exp merge), for both storage types:
+//   m* = max_s m_s,  w_s = 2^((m_s - m*) c),  out = sum_s w_s o_s / sum_s w_s l_s
+// The sum runs over s in a fixed order, so results are reproducible.
+struct CombineArgs {
+    const float* ws_o;
+    const float* ws_ml;
+    void* out;
+    int B, Hq, Hkv, G, R, MT, S, mrows, D, bf16;
+    float c;
+};
+
+__global__ __launch_bounds__(256) void attn_combine_kernel(CombineArgs a)
+{
+    const int d4n = a.D / 4;
+    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const long long total = (long long)a.Hkv * a.R * d4n;
+    if (idx >= total) return;
+    const int d4 = (int)(idx % d4n);
+    const long long hr = idx / d4n;
+    const int row = (int)(hr % a.R);
+    const int kh = (int)(hr / a.R);
+    const int mt = row / a.mrows, rit = row % a.mrows;
+    const size_t p0 = (((size_t)kh * a.MT + mt) * a.S) * a.mrows + rit;
+    float mstar = -INFINITY;
+    for (int s = 0; s < a.S; ++s) mstar = fmaxf(mstar, a.ws_ml[(p0 + (size_t)s * a.mrows) * 2]);
+    float l = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < a.S; ++s) {
+        const size_t pr = p0 + (size_t)s * a.mrows;
+        const float w = exp2f((a.ws_ml[pr * 2] - mstar) * a.c);
+        l = fmaf(a.ws_ml[pr * 2 + 1], w, l);
+        const float4 x = *reinterpret_cast<const float4*>(a.ws_o + pr * a.D + d4 * 4);
+        acc.x = fmaf(x.x, w, acc.x);
+        acc.y = fmaf(x.y, w, acc.y);
+        acc.z = fmaf(x.z, w, acc.z);
+        acc.w = fmaf(x.w, w, acc.w);
+    }
+    const float inv = 1.f / l;
+    const int nb = row / a.G, g = row % a.G;
+    const size_t off = ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * a.D + d4 * 4;
+    if (a.bf16) {
+        typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+        bf16x4 w;
+        w[0] = (__bf16)(acc.x * inv);
+        w[1] = (__bf16)(acc.y * inv);
+        w[2] = (__bf16)(acc.z * inv);
+        w[3] = (__bf16)(acc.w * inv);
+        *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(a.out) + off) = w;
+    } else {
+        *reinterpret_cast<float4*>(static_cast<float*>(a.out) + off) =
+            make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_attn_f32(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s)
+{
+    Args a;
+    a.q = static_cast<const float*>(p.q);
+    a.pk = static_cast<const float*>(p.prefix_k);
+    a.pv = static_cast<const float*>(p.prefix_v);
+    a.bk = static_cast<const float*>(p.block_k);
+    a.bv = static_cast<const float*>(p.block_v);
+    a.out = static_cast<float*>(p.out);
+    a.ws_o = static_cast<float*>(p.workspace);
+    a.ws_ml = reinterpret_cast<float*>(static_cast<char*>(p.workspace) + plan.ws_o_bytes);
+    a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
+    a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.S = plan.splits;
+    a.c = scale * 1.4426950408889634f;
+    if (plan.mtile_rows != RT) return hipErrorInvalidValue;
+    const dim3 grid(plan.MT, plan.splits, p.Hkv);
+    if (p.D == 128) hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(THREADS), 0, s, a);
+    else hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(THREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s)
+{
+    CombineArgs a;
+    a.ws_o = static_cast<const float*>(p.workspace);
+    a.ws_ml = reinterpret_cast<const float*>(static_cast<const char*>(p.workspace) + plan.ws_o_bytes);
+    a.out = p.out;
+    a.B = p.B; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = plan.G; a.R = plan.R; a.MT = plan.MT;
+    a.S = plan.splits; a.mrows = plan.mtile_rows; a.D = p.D; a.bf16 = (p.dtype == FDD_BF16);
+    a.c = scale * 1.4426950408889634f;
+    const long long total = (long long)p.Hkv * plan.R * (p.D / 4);
+    const int grid = (int)((total + 255) / 256);
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(grid), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace fdd

@@ -1,0 +1,74 @@
+// Rollout-fork bookkeeping: the private per-rollout state of forked rollouts.
+//
+// "Fork the KV cache N times" (paper, "Shared prefix"): the prefix is shared by
+// pointer and never copied, so a fork only replicates the block-sized private
+// arrays (block K/V, tokens, mask).  After an unmask step the K/V rows of the
+// newly committed positions are refreshed; with no model in scope the new row
+// is looked up in caller-provided tables by token id.
+#include "fdd_internal.h"
+
+namespace fdd {
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void fork_kernel(int N, size_t words, int vec, const uint32_t* src, uint32_t* dst)
+{
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (vec) {
+        const size_t n4 = words / 4;
+        const u32x4* s4 = reinterpret_cast<const u32x4*>(src);
+        u32x4* d4 = reinterpret_cast<u32x4*>(dst);
+        for (size_t i = i0; i < n4; i += stride) {
+            const u32x4 x = s4[i];
+            for (int n = 0; n < N; ++n) d4[(size_t)n * n4 + i] = x;
+        }
+    } else {
+        for (size_t i = i0; i < words; i += stride) {
+            const uint32_t x = src[i];
+            for (int n = 0; n < N; ++n) dst[(size_t)n * words + i] = x;
+        }
+    }
+}
+
+// one workgroup per block position; rows are Hkv*D elements = `row_vecs` 16-byte pieces
+__global__ __launch_bounds__(256) void kv_update_kernel(int T, int row_vecs, const int32_t* tokens, const uint8_t* committed,
+                                                         const u32x4* tk, const u32x4* tv, u32x4* bk, u32x4* bv)
+{
+    const size_t i = blockIdx.x;
+    if (!committed[i]) return;
+    int t = tokens[i] % T;
+    if (t < 0) t += T;
+    for (int c = threadIdx.x; c < row_vecs; c += blockDim.x) {
+        bk[i * row_vecs + c] = tk[(size_t)t * row_vecs + c];
+        bv[i * row_vecs + c] = tv[(size_t)t * row_vecs + c];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_fork_block(int N, size_t bytes, const void* src, void* dst, hipStream_t s)
+{
+    const size_t words = bytes / 4;
+    const int vec = (bytes % 16 == 0) && ((uintptr_t)src % 16 == 0) && ((uintptr_t)dst % 16 == 0);
+    const size_t items = vec ? words / 4 : words;
+    size_t grid = (items + 255) / 256;
+    if (grid > 2048) grid = 2048;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(fork_kernel, dim3((unsigned)grid), dim3(256), 0, s, N, words, vec,
+                       static_cast<const uint32_t*>(src), static_cast<uint32_t*>(dst));
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_update(const fdd_kv_update_params& p, hipStream_t s)
+{
+    const size_t es = p.dtype == FDD_BF16 ? 2 : 4;
+    const int row_vecs = (int)((size_t)p.Hkv * p.D * es / 16);
+    hipLaunchKernelGGL(kv_update_kernel, dim3((unsigned)(p.N * p.B)), dim3(256), 0, s, p.T, row_vecs, p.tokens, p.committed,
+                       static_cast<const u32x4*>(p.table_k), static_cast<const u32x4*>(p.table_v),
+                       static_cast<u32x4*>(p.block_k), static_cast<u32x4*>(p.block_v));
+    return hipGetLastError();
+}
+
+}  // namespace fdd

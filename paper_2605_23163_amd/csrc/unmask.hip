@@ -1,0 +1,302 @@
+// Confidence-threshold unmasking of one block per rollout.
+//
+// One iteration of "iteratively unmasks value positions" (paper, "Section
+// Diffusion (SD)"): masked, non-scaffold positions are the only ones touched
+// (Eq. 2; visible tokens stay fixed).  For each such position the row of V
+// logits is reduced to (arg max, largest softmax probability); a position
+// commits when that probability reaches tau, and a block that would commit
+// nothing commits its most confident eligible position.
+//
+// Two kernels:
+//   vocab_reduce  streams the logits rows of eligible positions once.  A row
+//                 is cut into `vsplits` pieces so that a few hundred rows
+//                 still fill 256 CUs; each piece is reduced by one workgroup
+//                 to (max, lowest arg max, sum exp(x - max)) with a one-pass
+//                 running-maximum sum.  (value, index) pairs are ordered by
+//                 value descending then index ascending through every
+//                 in-thread, cross-lane and cross-wave stage, so ties of
+//                 stored values (frequent in bf16) always resolve to the
+//                 lowest id.  Workgroups of non-eligible rows exit at once
+//                 and read nothing.
+//   block_select  one workgroup per rollout: merges the pieces of each
+//                 position in a fixed order (sum finished in fp64), applies
+//                 the tau test and the forced single commit, and writes
+//                 tokens / mask / confidences.
+#include "fdd_internal.h"
+
+namespace fdd {
+namespace {
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr int RTHREADS = 256;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct Partial {
+    float m;
+    int32_t arg;
+    float s;
+    int32_t pad;
+};
+
+struct Args {
+    const void* logits;
+    const uint8_t* scaffold;
+    uint8_t* mask;
+    int32_t* tokens;
+    float* conf;
+    int32_t* n_unmasked;
+    uint8_t* committed;
+    Partial* ws;
+    int N, B, vsplits;
+    long long V;
+    float tau;
+};
+
+struct Run {
+    float m;      // running maximum
+    int idx;      // lowest index attaining it
+    float s;      // sum of 2^((x - m) log2 e) over what was seen
+};
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// `b` is merged into `a`; on equal maxima the lower index wins.
+__device__ __forceinline__ void merge(Run& a, const Run& b)
+{
+    const bool take_b = (b.m > a.m) || (b.m == a.m && b.idx < a.idx);
+    const float M = fmaxf(a.m, b.m);
+    const float sa = (a.m == M) ? a.s : a.s * fast_exp2((a.m - M) * LOG2E);
+    const float sb = (b.m == M) ? b.s : b.s * fast_exp2((b.m - M) * LOG2E);
+    a.s = sa + sb;
+    a.m = M;
+    if (take_b) a.idx = b.idx;
+}
+
+template <int VEC>
+__device__ __forceinline__ void absorb(Run& r, const float (&x)[VEC], int v0)
+{
+    float cm = x[0];
+#pragma unroll
+    for (int j = 1; j < VEC; ++j) cm = fmaxf(cm, x[j]);
+    if (cm > r.m) {
+        // this thread walks the row in ascending order, so a strictly larger
+        // value is the only way its arg max can move
+        r.s *= fast_exp2((r.m - cm) * LOG2E);
+        r.m = cm;
+        int first = VEC - 1;
+#pragma unroll
+        for (int j = VEC - 2; j >= 0; --j) first = (x[j] == cm) ? j : first;
+        r.idx = v0 + first;
+    }
+    const float mc = r.m * LOG2E;
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < VEC; ++j) acc += fast_exp2(fmaf(x[j], LOG2E, -mc));
+    r.s += acc;
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+
+// T = uint16_t (bf16 bits) or float
+template <typename T>
+__global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    const int row = blockIdx.x / a.vsplits;
+    if (a.mask[row] != 1 || (a.scaffold && a.scaffold[row])) return;
+    const int piece = blockIdx.x % a.vsplits;
+    const long long per = (a.V + a.vsplits - 1) / a.vsplits;
+    const long long v_lo = piece * per;
+    const long long v_hi = min(a.V, v_lo + per);
+    const T* base = static_cast<const T*>(a.logits) + (size_t)row * (size_t)a.V;
+    const int tid = threadIdx.x;
+
+    Run r;
+    r.m = -INFINITY;
+    r.idx = 0x7fffffff;
+    r.s = 0.f;
+
+    if (v_lo < v_hi) {
+        // leading elements up to the first 16-byte boundary, then whole
+        // vectors, then the remainder; each thread visits ascending indices
+        const size_t e_lo = (size_t)row * (size_t)a.V + (size_t)v_lo;
+        long long head = (long long)((VEC - (e_lo % VEC)) % VEC);
+        if (head > v_hi - v_lo) head = v_hi - v_lo;
+        const long long body0 = v_lo + head;
+        const long long nvec = (v_hi - body0) / VEC;
+        const long long tail0 = body0 + nvec * VEC;
+
+        if (tid < head) {
+            float x[1] = {sizeof(T) == 2 ? bf16_to_f32(((const uint16_t*)base)[v_lo + tid]) : ((const float*)base)[v_lo + tid]};
+            absorb<1>(r, x, (int)(v_lo + tid));
+        }
+        const u32x4* vp = reinterpret_cast<const u32x4*>(base + body0);
+        for (long long i = tid; i < nvec; i += RTHREADS) {
+            const u32x4 raw = __builtin_nontemporal_load(vp + i);
+            float x[VEC];
+            if (sizeof(T) == 2) {
+                const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    x[2 * j] = __uint_as_float(w[j] << 16);
+                    x[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+                }
+            } else {
+                x[0] = __uint_as_float(raw.x);
+                x[1] = __uint_as_float(raw.y);
+                x[2] = __uint_as_float(raw.z);
+                x[3] = __uint_as_float(raw.w);
+            }
+            absorb<VEC>(r, x, (int)(body0 + i * VEC));
+        }
+        const long long ntail = v_hi - tail0;
+        if (tid < ntail) {
+            float x[1] = {sizeof(T) == 2 ? bf16_to_f32(((const uint16_t*)base)[tail0 + tid]) : ((const float*)base)[tail0 + tid]};
+            // tail indices are larger than anything this thread saw before
+            absorb<1>(r, x, (int)(tail0 + tid));
+        }
+    }
+
+    // wavefront reduction, then across the 4 wavefronts through LDS
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        Run o;
+        o.m = __shfl_xor(r.m, off, 64);
+        o.idx = __shfl_xor(r.idx, off, 64);
+        o.s = __shfl_xor(r.s, off, 64);
+        merge(r, o);
+    }
+    __shared__ Run part[RTHREADS / 64];
+    if ((tid & 63) == 0) part[tid >> 6] = r;
+    __syncthreads();
+    if (tid == 0) {
+        Run t = part[0];
+#pragma unroll
+        for (int w = 1; w < RTHREADS / 64; ++w) merge(t, part[w]);
+        Partial p;
+        p.m = t.m;
+        p.arg = t.idx;
+        p.s = t.s;
+        p.pad = 0;
+        a.ws[(size_t)row * a.vsplits + piece] = p;
+    }
+}
+
+constexpr int STHREADS = 256;
+
+__global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
+{
+    const int n = blockIdx.x;
+    const int tid = threadIdx.x;
+    const double tau = (double)a.tau;
+
+    int my_count = 0;
+    double best_conf = -1.0;     // confidences are positive
+    int best_b = 0x7fffffff;
+    int best_tok = -1;
+
+    for (int b = tid; b < a.B; b += STHREADS) {
+        const size_t i = (size_t)n * a.B + b;
+        const bool eligible = a.mask[i] == 1 && !(a.scaffold && a.scaffold[i]);
+        float conf_out = -INFINITY;
+        uint8_t com = 0;
+        if (eligible) {
+            const Partial* p = a.ws + i * a.vsplits;
+            // pieces cover ascending index ranges: strict '>' keeps the lowest id
+            float M = p[0].m;
+            int arg = p[0].arg;
+            for (int s = 1; s < a.vsplits; ++s)
+                if (p[s].m > M) { M = p[s].m; arg = p[s].arg; }
+            double z = 0.0;
+            for (int s = 0; s < a.vsplits; ++s)
+                if (p[s].s > 0.f) z += (double)p[s].s * exp2((double)(p[s].m - M) * 1.4426950408889634);
+            const double conf = 1.0 / z;
+            conf_out = (float)conf;
+            if (conf >= tau) {
+                a.tokens[i] = arg;
+                a.mask[i] = 0;
+                com = 1;
+                ++my_count;
+            }
+            if (conf > best_conf) { best_conf = conf; best_b = b; best_tok = arg; }   // ascending b per thread
+        }
+        a.conf[i] = conf_out;
+        if (a.committed) a.committed[i] = com;
+    }
+
+    __shared__ int s_count[STHREADS];
+    __shared__ double s_conf[STHREADS];
+    __shared__ int s_b[STHREADS];
+    __shared__ int s_tok[STHREADS];
+    s_count[tid] = my_count;
+    s_conf[tid] = best_conf;
+    s_b[tid] = best_b;
+    s_tok[tid] = best_tok;
+    __syncthreads();
+    for (int off = STHREADS / 2; off >= 1; off >>= 1) {
+        if (tid < off) {
+            s_count[tid] += s_count[tid + off];
+            const bool take = (s_conf[tid + off] > s_conf[tid]) ||
+                              (s_conf[tid + off] == s_conf[tid] && s_b[tid + off] < s_b[tid]);
+            if (take) {
+                s_conf[tid] = s_conf[tid + off];
+                s_b[tid] = s_b[tid + off];
+                s_tok[tid] = s_tok[tid + off];
+            }
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        int count = s_count[0];
+        if (count == 0 && s_tok[0] >= 0) {
+            // nothing reached tau: commit the most confident eligible position
+            const size_t i = (size_t)n * a.B + s_b[0];
+            a.tokens[i] = s_tok[0];
+            a.mask[i] = 0;
+            if (a.committed) a.committed[i] = 1;
+            count = 1;
+        }
+        if (a.n_unmasked) a.n_unmasked[n] = count;
+    }
+}
+
+}  // namespace
+
+bool make_unmask_plan(const fdd_unmask_params& p, UnmaskPlan* plan)
+{
+    if (p.N <= 0 || p.B <= 0 || p.V <= 0) return false;
+    const long long rows = (long long)p.N * p.B;
+    const long long es = p.dtype == FDD_BF16 ? 2 : 4;
+    long long by_size = (p.V * es) / 16384;     // keep pieces at 16 KiB or more
+    if (by_size < 1) by_size = 1;
+    long long want = (8192 + rows - 1) / rows;  // enough workgroups to fill 256 CUs several times
+    if (want < 1) want = 1;
+    long long vs = want < by_size ? want : by_size;
+    if (vs > 64) vs = 64;
+    plan->vsplits = (int)vs;
+    plan->ws_bytes = (size_t)rows * (size_t)vs * sizeof(Partial);
+    return true;
+}
+
+hipError_t launch_unmask(const fdd_unmask_params& p, const UnmaskPlan& plan, hipStream_t s)
+{
+    Args a;
+    a.logits = p.logits;
+    a.scaffold = p.scaffold_mask;
+    a.mask = p.mask;
+    a.tokens = p.tokens;
+    a.conf = p.confidences;
+    a.n_unmasked = p.n_unmasked;
+    a.committed = p.committed;
+    a.ws = static_cast<Partial*>(p.workspace);
+    a.N = p.N; a.B = p.B; a.vsplits = plan.vsplits; a.V = p.V; a.tau = p.tau;
+    const dim3 grid((unsigned)(plan.vsplits * p.N * p.B));
+    if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_reduce_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
+    else hipLaunchKernelGGL(vocab_reduce_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(block_select_kernel, dim3(p.N), dim3(STHREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace fdd

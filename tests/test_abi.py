@@ -1,0 +1,120 @@
+"""The C ABI on a machine without a GPU: the library loads, exports what
+include/fdd.h declares, sizes workspaces on the host, and turns every
+host-detectable mistake into an error code without launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_23163_amd import binding as bd
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(bd.library_path()):
+        from paper_2605_23163_amd import build
+        build.build()
+    return bd.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fdd.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fdd_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(bd.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_empty_error(lib):
+    assert lib.fdd_version() == 100
+
+
+def attn(**kw):
+    p = bd.AttnParams()
+    base = dict(N=1, B=32, L=2048, Hq=28, Hkv=4, D=128, dtype=bd.FDD_BF16, scale=0.0, q=256, prefix_k=512,
+                prefix_v=768, block_k=1024, block_v=1280, out=1536, workspace=4096, workspace_bytes=1 << 30)
+    base.update(kw)
+    for k, v in base.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_attn_workspace_is_host_arithmetic(lib):
+    p = attn()
+    w = lib.fdd_block_attn_workspace(C.byref(p))
+    assert w > 0 and w % 256 == 0
+    p1 = attn(splits=1)
+    assert lib.fdd_block_attn_workspace(C.byref(p1)) == 0
+    p4 = attn(splits=4)
+    # 4 KV heads x 1 M-tile x 4 splits x 256 rows x (128 + 2) floats
+    assert lib.fdd_block_attn_workspace(C.byref(p4)) == 4 * 4 * 256 * 130 * 4
+    assert lib.fdd_block_attn_workspace(C.byref(attn(Hq=30))) == 0     # invalid -> 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(N=0), 2), (dict(B=-1), 2), (dict(L=-1), 2), (dict(Hq=30), 2), (dict(dtype=7), 3), (dict(D=96), 4),
+    (dict(splits=65), 4), (dict(reserved=1), 4), (dict(q=None), 1), (dict(out=None), 1), (dict(prefix_k=None), 1),
+    (dict(block_v=None), 1), (dict(q=264), 4), (dict(out=256), 4), (dict(workspace=None), 5),
+    (dict(workspace=4100), 5), (dict(workspace_bytes=16), 5), (dict(scale=float("nan")), 4),
+])
+def test_attn_rejects_bad_arguments_without_launching(lib, kw, code):
+    p = attn(**kw)
+    assert lib.fdd_block_attn(C.byref(p)) == code
+    assert lib.fdd_last_error().decode().startswith("fdd_block_attn:")
+    assert lib.fdd_block_attn(None) == 1
+
+
+def unmask(**kw):
+    p = bd.UnmaskParams()
+    base = dict(N=8, B=32, V=152064, dtype=bd.FDD_BF16, tau=0.9, logits=256, mask=512, tokens=768, confidences=1024,
+                workspace=4096, workspace_bytes=1 << 30)
+    base.update(kw)
+    for k, v in base.items():
+        setattr(p, k, v)
+    return p
+
+
+def test_unmask_workspace_and_errors(lib):
+    assert lib.fdd_unmask_workspace(C.byref(unmask())) > 0
+    assert lib.fdd_unmask_workspace(C.byref(unmask(V=0))) == 0
+    for kw, code in [(dict(N=0), 2), (dict(V=0), 2), (dict(V=1 << 31), 2), (dict(dtype=3), 3), (dict(logits=None), 1),
+                     (dict(mask=None), 1), (dict(tokens=None), 1), (dict(confidences=None), 1), (dict(logits=260), 4),
+                     (dict(workspace=None), 5), (dict(workspace_bytes=8), 5), (dict(tau=float("nan")), 4)]:
+        assert lib.fdd_unmask_step(C.byref(unmask(**kw))) == code, kw
+        assert lib.fdd_last_error().decode().startswith("fdd_unmask_step:")
+    assert lib.fdd_unmask_step(None) == 1
+
+
+def test_bookkeeping_errors(lib):
+    assert lib.fdd_fork_block(4, 64, None, 4096, None) == 1
+    assert lib.fdd_fork_block(0, 64, 256, 4096, None) == 2
+    assert lib.fdd_fork_block(4, 6, 256, 4096, None) == 4
+    assert lib.fdd_fork_block(4, 64, 256, 300, None) == 4        # overlap
+    p = bd.KvUpdateParams()
+    for k, v in dict(N=2, B=4, Hkv=4, D=128, T=16, dtype=1, tokens=256, committed=512, table_k=1024, table_v=2048,
+                     block_k=4096, block_v=8192).items():
+        setattr(p, k, v)
+    p.T = 0
+    assert lib.fdd_block_kv_update(C.byref(p)) == 2
+    p.T, p.table_k = 16, None
+    assert lib.fdd_block_kv_update(C.byref(p)) == 1
+    p.table_k, p.dtype = 1024, 9
+    assert lib.fdd_block_kv_update(C.byref(p)) == 3
+    assert lib.fdd_block_kv_update(None) == 1
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    q = torch.zeros(1, 8, 4, 64)
+    k = torch.zeros(16, 1, 64)
+    b = torch.zeros(1, 8, 1, 64)
+    with pytest.raises(ValueError, match="GPU memory"):
+        bd.fdd_block_attn(q, k, k, b, b, out=torch.zeros_like(q))

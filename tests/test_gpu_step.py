@@ -1,0 +1,55 @@
+"""The whole denoise step chained on the GPU vs the oracle: attention,
+unmask, K/V refresh, over several consecutive steps on one shared prefix
+(the shape of the long multi-camera configuration, reduced so that the
+oracle finishes in seconds)."""
+import numpy as np
+import pytest
+import torch
+
+import fdd_workloads as W
+from tests.gpu_util import print_case, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def test_multi_step_denoise_matches_oracle(oracle):
+    import paper_2605_23163_amd as F
+    w = W.Workload("mini5", N=4, B=64, L=1200, Hq=28, Hkv=4, D=128, dtype=W.BF16, V=8192, logit_std=2.0,
+                   spike=12.0, spike_frac=0.3, scaffold_frac=0.30, tau=0.9, steps=4, table_rows=512, seed=55)
+    print_case(test="multi_step", workload=w.name)
+    d = W.full_step_inputs(w)
+    tau = float(np.float32(w.tau))
+    # oracle state
+    o = {k: d[k].copy() for k in ("block_k", "block_v", "tokens", "mask")}
+    # device state; the N rollouts start as forks of rollout 0's block state
+    g = {k: to_dev(d[k]) for k in ("q", "prefix_k", "prefix_v", "table_k", "table_v")}
+    g["scaffold"] = torch.from_numpy(d["scaffold_mask"]).cuda()
+    for k in ("block_k", "block_v", "tokens", "mask"):
+        o[k][:] = o[k][:1]
+        g[k] = F.fdd_fork_block(to_dev(d[k][0]), w.N)
+    prefix_ptr = g["prefix_k"].data_ptr()
+    total_commits = 0
+    for step in range(w.steps):
+        logits = W.step_logits(w, o["mask"], d["logit_rngs"][step])
+        ref_out = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], o["block_k"], o["block_v"])
+        r = oracle.unmask_step(logits, o["mask"], d["scaffold_mask"], o["tokens"], tau)
+        o["tokens"], o["mask"] = r["tokens"], r["mask"]
+        o["block_k"], o["block_v"] = oracle.block_kv_update(o["tokens"], r["committed"], d["table_k"], d["table_v"],
+                                                            o["block_k"], o["block_v"])
+        out = F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], g["block_k"], g["block_v"], g["scaffold"])
+        _, conf, nun, com = F.fdd_unmask_step(to_dev(logits), g["mask"], g["scaffold"], tau, g["tokens"])
+        F.fdd_block_kv_update(g["tokens"], com, g["table_k"], g["table_v"], g["block_k"], g["block_v"])
+        torch.cuda.synchronize()
+        err = np.abs(to_f64(out) - ref_out).max()
+        assert err <= 2e-2, f"step {step}: attention max-abs {err}"
+        near = np.abs(r["confidences"] - tau) < 1e-3
+        assert not near.any(), "seed produced a near-tau confidence; pick another"
+        np.testing.assert_array_equal(g["tokens"].cpu().numpy(), o["tokens"])
+        np.testing.assert_array_equal(g["mask"].cpu().numpy(), o["mask"])
+        np.testing.assert_array_equal(nun.cpu().numpy(), r["n_unmasked"])
+        assert torch.equal(g["block_k"], to_dev(o["block_k"])) and torch.equal(g["block_v"], to_dev(o["block_v"]))
+        total_commits += int(r["n_unmasked"].sum())
+    assert g["prefix_k"].data_ptr() == prefix_ptr        # the prefix was never copied or replaced
+    assert total_commits >= w.steps * w.N                # at least one commit per block per step
+    sc = d["scaffold_mask"] == 1
+    np.testing.assert_array_equal(g["tokens"].cpu().numpy()[sc], d["tokens"][sc])   # scaffold never rewritten
