@@ -20,6 +20,9 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.join(ROOT, "include"),
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+# The attention kernels never produce a NaN (masked scores are -inf and every
+# inf - inf is avoided by construction), so max/min need no NaN quieting.
+EXTRA = {"attn_bf16.hip": ["-fno-honor-nans", "-mno-amdgpu-ieee"]}
 
 
 def sources():
@@ -43,10 +46,11 @@ def build(asm: bool = False, jobs: int = 4) -> str:
     for src in sources():
         obj = os.path.join(bdir, os.path.basename(src)[:-4] + ".o")
         objs.append(obj)
-        cmd = [HIPCC, *FLAGS, "-c", src, "-o", obj]
-        if asm:
-            cmd += ["-save-temps=obj"]
+        cmd = [HIPCC, *FLAGS, *EXTRA.get(os.path.basename(src), []), "-c", src, "-o", obj]
         cmds.append(cmd)
+        if asm:   # device assembly next to the objects, for inspection
+            cmds.append([HIPCC, *FLAGS, *EXTRA.get(os.path.basename(src), []), "-S", "--offload-device-only",
+                         src, "-o", obj[:-2] + ".s"])
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         list(ex.map(_run, cmds))
     tmp = LIB + f".{os.getpid()}.tmp"

@@ -19,18 +19,35 @@
 //     operand of O^T += V^T P^T, so P never leaves the register file and the
 //     accumulator keeps one query row per lane: its rescale is a per-lane
 //     scalar multiply.
-//   * V^T needs the key index contiguous per lane, so V tiles are transposed
-//     on their way into LDS ([d][key], keys permuted so the 8 keys a lane
-//     feeds to one MFMA are 16 contiguous bytes).  K tiles are stored
-//     [key][d].  Both use a 16-byte row pad that makes the 128-bit fragment
-//     reads bank-conflict free.
+//   * K and V tiles are staged in LDS as they lie in memory, [key][d], with
+//     16-byte stores.  The K fragments of S^T = K Q^T are plain 128-bit reads.
+//     O^T += V^T P^T needs, per lane, 8 keys of one channel: those fragments
+//     come from the gfx950 LDS transpose read (ds_read_b64_tr_b16), which
+//     hands lane i of a 16-lane group column i of a 4 x 16 block, i.e. 4
+//     consecutive keys of channel i.  Row pads (16 bytes for K, 64 for V) make
+//     both kinds of read bank-conflict free.
+//   * Full prefix tiles run through a software-pipelined loop written as 32
+//     slots per tile, one per MFMA.  Each slot also carries a slice of vector
+//     ALU work that does not depend on that MFMA: while the matrix pipe
+//     produces the scores of tile i+1 and then the P V products of tile i,
+//     the vector ALUs reduce the row maximum of tile i, take its exponentials
+//     and round them to bf16.  One wavefront can only issue a vector
+//     instruction every other issue slot, so two wavefronts per SIMD running
+//     this same mix are what fills both pipes.  K runs one tile ahead of V in
+//     LDS (two buffers each), global loads another tile ahead in registers,
+//     and LDS fragments are requested two MFMAs before their use.
+//   * The softmax reference value of a row is only raised when the running
+//     maximum outgrows it by more than 2^8; in between probabilities may
+//     exceed 1, which fp32 sums and bf16 relative precision do not mind, and
+//     the accumulator rescale becomes a rare wave-uniform branch.  The result
+//     is mathematically the same softmax.
 //   * The prefix is cut into `splits` pieces along L; each piece keeps the
 //     streaming-softmax state (m, l, o) per row and writes it as an fp32
 //     partial that a second small kernel merges (log-sum-exp merge).  With
 //     one piece the kernel normalises and writes bf16 output directly.
-//   * The in-block tail runs through the same tile loop: after the prefix
-//     tiles, the workgroup stages the block K/V of each rollout its rows
-//     belong to and masks the rows of other rollouts to -inf.
+//   * A ragged last prefix tile and the in-block tail go through a simpler
+//     masked path: the workgroup stages the block K/V of each rollout its
+//     rows belong to and masks the rows of other rollouts to -inf.
 #include "fdd_internal.h"
 
 namespace fdd {
@@ -42,7 +59,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 constexpr int KT = 64;           // keys per tile
-constexpr int VROW = KT * 2 + 16;  // bytes per row of the transposed V tile
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 
 struct Args {
     const uint16_t* q;
@@ -70,19 +87,32 @@ template <int D, int WAVES>
 struct Cfg {
     static constexpr int THREADS = WAVES * 64;
     static constexpr int KROW = D * 2 + 16;             // bytes per K row in LDS
+    static constexpr int VROW = D * 2 + 64;             // bytes per V row in LDS
     static constexpr int K_BYTES = KT * KROW;
-    static constexpr int V_BYTES = D * VROW;
+    static constexpr int V_BYTES = KT * VROW;
     static constexpr int BUF_BYTES = K_BYTES + V_BYTES;
     static constexpr int K_CHUNKS = KT * (D / 8);        // 16-byte pieces of a K tile
     static constexpr int K_PER_THREAD = K_CHUNKS / THREADS;
-    static constexpr int V_TASKS = (KT / 4) * (D / 2);   // (4 keys) x (2 channels) pieces
-    static constexpr int V_PER_THREAD = V_TASKS / THREADS;
-    static_assert(K_CHUNKS % THREADS == 0 && V_TASKS % THREADS == 0, "tile must divide over the workgroup");
+    static_assert(K_CHUNKS % THREADS == 0, "tile must divide over the workgroup");
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+// value held by the lane 32 positions away (the other half of the wavefront)
+__device__ __forceinline__ float other_half(float x)
+{
+    const unsigned u = __builtin_bit_cast(unsigned, x);
+    // swaps lanes 32..63 of the first operand with lanes 0..31 of the second
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
+}
+
+// Nothing is scheduled across this point: the source order of the pieces it
+// separates is the order the hardware sees.
+#define FDD_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+// Forces a value to exist at this point of the instruction stream, so that
+// the vector work of a slot is not sunk towards its first use.
+#define FDD_PIN(x) asm volatile("" : "+v"(x))
 
 template <int D, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
@@ -172,59 +202,48 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
 
     // ---- global -> register staging of one tile -----------------------------
     u32x4 kreg[C::K_PER_THREAD];
-    uint32_t vreg[C::V_PER_THREAD][4];
+    u32x4 vreg[C::K_PER_THREAD];
 
-    auto load_tile = [&](const Tile& t) {
+    // 16-byte pieces, consecutive lanes along a row; rows beyond `valid` are zero.
+    auto load_rows = [&](u32x4 (&reg)[C::K_PER_THREAD], const uint16_t* base, int valid, bool full) {
 #pragma unroll
         for (int i = 0; i < C::K_PER_THREAD; ++i) {
             const int c = tid + i * C::THREADS;
             const int key = c / (D / 8);
             const int col = c % (D / 8);
             u32x4 x = {0u, 0u, 0u, 0u};
-            if (key < t.valid) x = *reinterpret_cast<const u32x4*>(t.k + (size_t)key * kv_stride + col * 8);
-            kreg[i] = x;
-        }
-#pragma unroll
-        for (int i = 0; i < C::V_PER_THREAD; ++i) {
-            const int task = tid + i * C::THREADS;
-            const int dp = task % (D / 2);
-            const int kg = task / (D / 2);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int key = kg * 4 + j;
-                uint32_t x = 0u;
-                if (key < t.valid) x = *reinterpret_cast<const uint32_t*>(t.v + (size_t)key * kv_stride + dp * 2);
-                vreg[i][j] = x;
-            }
+            if (full || key < valid) x = *reinterpret_cast<const u32x4*>(base + (size_t)key * kv_stride + col * 8);
+            reg[i] = x;
         }
     };
-
-    auto store_tile = [&](int buf) {
-        unsigned char* kl = lds + buf * C::BUF_BYTES;
-        unsigned char* vl = kl + C::K_BYTES;
+    auto store_rows = [&](const u32x4 (&reg)[C::K_PER_THREAD], unsigned char* tile, int row_bytes) {
 #pragma unroll
         for (int i = 0; i < C::K_PER_THREAD; ++i) {
             const int c = tid + i * C::THREADS;
             const int key = c / (D / 8);
             const int col = c % (D / 8);
-            *reinterpret_cast<u32x4*>(kl + key * C::KROW + col * 16) = kreg[i];
+            *reinterpret_cast<u32x4*>(tile + key * row_bytes + col * 16) = reg[i];
         }
-#pragma unroll
-        for (int i = 0; i < C::V_PER_THREAD; ++i) {
-            const int task = tid + i * C::THREADS;
-            const int dp = task % (D / 2);
-            const int kg = task / (D / 2);
-            // keys 4kg..4kg+3 of channels 2dp and 2dp+1 -> two 8-byte rows of V^T.
-            // Key groups are stored with bits 0 and 1 of kg swapped, so that the
-            // 8 keys one lane feeds to one MFMA k-step sit in 16 contiguous bytes.
-            const int pg = (kg & ~3) | ((kg & 1) << 1) | ((kg & 2) >> 1);
-            const uint32_t x0 = vreg[i][0], x1 = vreg[i][1], x2 = vreg[i][2], x3 = vreg[i][3];
-            u32x2 even = {(x0 & 0xffffu) | (x1 << 16), (x2 & 0xffffu) | (x3 << 16)};
-            u32x2 odd = {(x0 >> 16) | (x1 & 0xffff0000u), (x2 >> 16) | (x3 & 0xffff0000u)};
-            unsigned char* p = vl + (2 * dp) * VROW + pg * 8;
-            *reinterpret_cast<u32x2*>(p) = even;
-            *reinterpret_cast<u32x2*>(p + VROW) = odd;
-        }
+    };
+    auto load_k = [&](const uint16_t* kp, int valid, bool full) { load_rows(kreg, kp, valid, full); };
+    auto load_v = [&](const uint16_t* vp, int valid, bool full) { load_rows(vreg, vp, valid, full); };
+    auto store_k = [&](int buf) { store_rows(kreg, lds + buf * C::K_BYTES, C::KROW); };
+    auto store_v = [&](int buf) { store_rows(vreg, lds + 2 * C::K_BYTES + buf * C::V_BYTES, C::VROW); };
+
+    // V^T fragment of one P V MFMA (16-key step t4, channel block db) by two
+    // transpose reads.  In a 16-lane group, lane 4j+q points at 4 channels of
+    // key row j; the read returns to lane i the 4 keys of channel i.  Element
+    // e of the fragment is key 16 t4 + 8 (e/4) + 4 half + e%4, the key order of
+    // the probabilities in the S^T accumulator.
+    const int tr_lane_off = ((half * 4 + ((lane & 15) >> 2)) * C::VROW) + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+    auto v_frag = [&](const unsigned char* vtile, int t4, int db) -> bf16x8 {
+        typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+        const unsigned char* p0 = vtile + tr_lane_off + (t4 * 16) * C::VROW + db * 64;
+        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0));
+        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0 + 8 * C::VROW));
+        typedef short i16x8 __attribute__((ext_vector_type(8)));
+        const i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        return __builtin_bit_cast(bf16x8, both);
     };
 
     // ---- streaming-softmax state: one query row per lane --------------------
@@ -233,26 +252,226 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-    float m_run = -INFINITY;   // running maximum of the raw scores
+    float m_ref = -INFINITY;   // reference value the exponentials are taken against (raw score units)
     float l_run = 0.f;         // this lane's share of the running sum
 
-    auto compute_tile = [&](int buf, const Tile& t) {
-        const unsigned char* kl = lds + buf * C::BUF_BYTES;
-        const unsigned char* vl = kl + C::K_BYTES;
-        f32x16 s[2];
+    // scores of one 32-key block: S^T[key, row] = K[key, :] . Q[row, :]
+    auto qk_block = [&](const unsigned char* kl, int kb, f32x16& s) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kl + (kb * 32 + l32) * C::KROW + ks * 32 + half * 16);
-                s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
-            }
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kl + (kb * 32 + l32) * C::KROW + ks * 32 + half * 16);
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
         }
-        // register v of block kb is key kb*32 + (v/4)*8 + half*4 + v%4
-        const bool row_sees = (t.rollout < 0) || (t.rollout == my_rollout);
-        if (t.valid < KT || t.rollout >= 0) {
+    };
+    // maximum of a row's 64 scores (both halves of the wavefront agree on it)
+    auto row_max = [&](const f32x16& s0, const f32x16& s1) -> float {
+        float mx = fmaxf(s0[0], s1[0]);
+#pragma unroll
+        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s0[v], s1[v]));
+        return fmaxf(mx, other_half(mx));
+    };
+    // raise the reference when the tile maximum outgrew it by more than 2^8
+    auto update_reference = [&](float mx) {
+        // also true for the first tile (m_ref = -inf); never evaluates inf - inf
+        const bool need = (mx > m_ref) && ((mx - m_ref) * a.c > 8.f);
+        if (__any(need)) {
+            const float m_new = fmaxf(m_ref, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2((m_ref - m_use) * a.c);
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+            m_ref = m_new;
+        }
+    };
+    // probabilities of one 32-key block, rounded to bf16 as two MFMA B operands
+    auto exp_block = [&](const f32x16& s, float mc, bf16x8& p0, bf16x8& p1) {
+        float acc = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float p = fast_exp2(fmaf(s[v], a.c, -mc));
+            acc += p;
+            if (v < 8) p0[v] = (__bf16)p; else p1[v - 8] = (__bf16)p;
+        }
+        l_run += acc;
+    };
+    // O^T += V^T P^T for the two 16-key steps of one 32-key block
+    auto pv_block = [&](const unsigned char* vtile, int kb, const bf16x8& p0, const bf16x8& p1) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int db = 0; db < DB; ++db) {
+                const bf16x8 vf = v_frag(vtile, kb * 2 + u, db);
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, u == 0 ? p0 : p1, o[db], 0, 0, 0);
+            }
+    };
+
+    // ---- fast path: full prefix tiles, software pipelined ---------------------
+    // F leading tiles of this piece are complete 64-key prefix tiles.
+    const int F = (n_prefix > 0 && (t0 + n_prefix) * KT > a.L) ? n_prefix - 1 : n_prefix;
+    const uint16_t* pk0 = a.pk + (size_t)t0 * KT * kv_stride + (size_t)kh * D;
+    const uint16_t* pv0 = a.pv + (size_t)t0 * KT * kv_stride + (size_t)kh * D;
+    const size_t tile_elems = (size_t)KT * kv_stride;
+    unsigned char* const kbuf0 = lds;
+    unsigned char* const vbuf0 = lds + 2 * C::K_BYTES;
+    bf16x8 p[4];      // probabilities of a tile as MFMA B operands, one per 16-key step
+
+    if (F > 0) {
+        // prologue: K(0), V(0) and K(1) into LDS, scores of tile 0
+        load_k(pk0, KT, true);
+        load_v(pv0, KT, true);
+        store_k(0);
+        store_v(0);
+        load_k(pk0 + (size_t)min(1, F - 1) * tile_elems, KT, true);
+        store_k(1);
+        __syncthreads();
+        f32x16 sa[2], sb[2];
+        qk_block(kbuf0, 0, sa[0]);
+        qk_block(kbuf0, 1, sa[1]);
+        __syncthreads();   // K buffer 0 is overwritten at the end of the first step
+
+        // One pipelined step: probabilities and P V of tile i from s_cur while
+        // the scores of tile i+1 go to s_nxt; K(i+2) and V(i+1) are fetched.
+        //   slots  0- 7  S(i+1) first 32 keys   ||  row maximum of tile i
+        //   slots  8-15  S(i+1) second 32 keys  ||  exp of the first 32 keys
+        //   slots 16-23  P V first 32 keys      ||  exp of the second 32 keys
+        //   slots 24-31  P V second 32 keys     ||  staging of the fetched tiles
+        auto step = [&](int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], bool has_next) {
+            load_k(pk0 + (size_t)min(i + 2, F - 1) * tile_elems, KT, true);
+            load_v(pv0 + (size_t)min(i + 1, F - 1) * tile_elems, KT, true);
+            const unsigned char* kl = kbuf0 + ((i + 1) & 1) * C::K_BYTES + l32 * C::KROW + half * 16;
+            const unsigned char* vl = vbuf0 + (i & 1) * C::V_BYTES;
+            auto kfrag = [&](int kb, int ks) {
+                return *reinterpret_cast<const bf16x8*>(kl + kb * 32 * C::KROW + ks * 32);
+            };
+            // P V slot j of block kb: 16-key step j / DB, channel block j % DB
+            auto vfrag = [&](int kb, int j) { return v_frag(vl, kb * 2 + j / DB, j % DB); };
+            bf16x8 f[3];
+            FDD_SCHED_FENCE();
+
+            // ---- slots 0-7 ----
+            float mx = -INFINITY;
+            if (has_next) {
+                f[0] = kfrag(0, 0);
+                f[1] = kfrag(0, 1);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s_nxt[0][v] = 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                if (has_next) {
+                    if (j + 2 < KS) f[(j + 2) % 3] = kfrag(0, j + 2);
+                    s_nxt[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[0], 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = j * (16 / KS); v < (j + 1) * (16 / KS); ++v) {
+                    mx = fmaxf(fmaxf(mx, s_cur[0][v]), s_cur[1][v]);
+                }
+                FDD_PIN(mx);
+                FDD_SCHED_FENCE();
+            }
+            mx = fmaxf(mx, other_half(mx));
+            update_reference(mx);
+            const float mc = ((m_ref == -INFINITY) ? 0.f : m_ref) * a.c;
+            float acc = 0.f;
+            u32x4 pw[4];     // the B operands of P V as packed words
+            // four probabilities of block kb (registers 4e .. 4e+3), rounded into the B operands
+            auto exp_quad = [&](int kb, int e) {
+                float pr[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) pr[t] = fast_exp2(fmaf(s_cur[kb][4 * e + t], a.c, -mc));
+                acc += (pr[0] + pr[1]) + (pr[2] + pr[3]);
+                typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+                bf16x2 lo = {(__bf16)pr[0], (__bf16)pr[1]}, hi = {(__bf16)pr[2], (__bf16)pr[3]};
+                uint32_t ulo = __builtin_bit_cast(uint32_t, lo), uhi = __builtin_bit_cast(uint32_t, hi);
+                FDD_PIN(ulo);
+                FDD_PIN(uhi);
+                FDD_PIN(acc);
+                pw[kb * 2 + e / 2][(e & 1) * 2] = ulo;
+                pw[kb * 2 + e / 2][(e & 1) * 2 + 1] = uhi;
+            };
+            FDD_SCHED_FENCE();
+
+            // ---- slots 8-15 ----
+            if (has_next) {
+                f[0] = kfrag(1, 0);
+                f[1] = kfrag(1, 1);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s_nxt[1][v] = 0.f;
+            }
+#pragma unroll
+            for (int j = 0; j < KS; ++j) {
+                if (has_next) {
+                    if (j + 2 < KS) f[(j + 2) % 3] = kfrag(1, j + 2);
+                    s_nxt[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[1], 0, 0, 0);
+                }
+                if ((j * 4) % KS == 0) exp_quad(0, j * 4 / KS);
+                FDD_SCHED_FENCE();
+            }
+            p[0] = __builtin_bit_cast(bf16x8, pw[0]);
+            p[1] = __builtin_bit_cast(bf16x8, pw[1]);
+
+            // ---- slots 16-23 ----
+            constexpr int PVS = 2 * DB;      // P V MFMAs per 32-key block
+            f[0] = vfrag(0, 0);
+            f[1] = vfrag(0, 1);
+#pragma unroll
+            for (int j = 0; j < PVS; ++j) {
+                if (j + 2 < PVS) f[(j + 2) % 3] = vfrag(0, j + 2);
+                o[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], p[j / DB], o[j % DB], 0, 0, 0);
+                if ((j * 4) % PVS == 0) exp_quad(1, j * 4 / PVS);
+                FDD_SCHED_FENCE();
+            }
+            p[2] = __builtin_bit_cast(bf16x8, pw[2]);
+            p[3] = __builtin_bit_cast(bf16x8, pw[3]);
+            l_run += acc;
+
+            // ---- slots 24-31 ---- (the buffers written here were last read in the previous step)
+            f[0] = vfrag(1, 0);
+            f[1] = vfrag(1, 1);
+#pragma unroll
+            for (int j = 0; j < PVS; ++j) {
+                if (j + 2 < PVS) f[(j + 2) % 3] = vfrag(1, j + 2);
+                o[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], p[2 + j / DB], o[j % DB], 0, 0, 0);
+                if (j == 1) store_k(i & 1);
+                if (j == PVS / 2 + 1) store_v((i + 1) & 1);
+                FDD_SCHED_FENCE();
+            }
+            __syncthreads();
+        };
+        int i = 0;
+        for (; i + 2 < F; i += 2) {
+            step(i, sa, sb, true);
+            step(i + 1, sb, sa, true);
+        }
+        if (i + 2 == F) {
+            step(i, sa, sb, true);
+            step(i + 1, sb, sa, false);
+        } else {
+            step(i, sa, sb, false);
+        }
+    }
+    f32x16 s[2];      // scores of a masked tile
+
+    // ---- masked path: ragged last prefix tile and the in-block tail ------------
+    for (int i = F; i < n_tiles; ++i) {
+        const Tile t = tile_at(i);
+        load_k(t.k, t.valid, false);
+        load_v(t.v, t.valid, false);
+        store_k(0);
+        store_v(0);
+        __syncthreads();
+        const bool wave_active = wave_has_rows &&
+            (t.rollout < 0 || (t.rollout >= wave_n_lo && t.rollout <= wave_n_hi));
+        if (wave_active) {
+            qk_block(kbuf0, 0, s[0]);
+            qk_block(kbuf0, 1, s[1]);
+            // register v of block kb is key kb*32 + (v/4)*8 + half*4 + v%4
+            const bool row_sees = (t.rollout < 0) || (t.rollout == my_rollout);
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -260,63 +479,16 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                     const int key = kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
                     if (!row_sees || key >= t.valid) s[kb][v] = -INFINITY;
                 }
+            update_reference(row_max(s[0], s[1]));
+            const float mc = ((m_ref == -INFINITY) ? 0.f : m_ref) * a.c;
+            exp_block(s[0], mc, p[0], p[1]);
+            exp_block(s[1], mc, p[2], p[3]);
+            pv_block(vbuf0, 0, p[0], p[1]);
+            pv_block(vbuf0, 1, p[2], p[3]);
         }
-        float mx = s[0][0];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
-        mx = fmaxf(mx, other_half(mx));
-        const float m_new = fmaxf(m_run, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2((m_run - m_use) * a.c);
-        const float mc = m_use * a.c;
-        float psum = 0.f;
-        bf16x8 pf[4];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const float p = fast_exp2(fmaf(s[kb][v], a.c, -mc));
-                psum += p;
-                pf[kb * 2 + (v >> 3)][v & 7] = (__bf16)p;
-            }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-#pragma unroll
-        for (int t4 = 0; t4 < 4; ++t4)
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const bf16x8 vf = *reinterpret_cast<const bf16x8*>(vl + (db * 32 + l32) * VROW + (t4 * 16 + half * 8) * 2);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[t4], o[db], 0, 0, 0);
-            }
-    };
-
-    // ---- main loop: double-buffered tiles ------------------------------------
-    if (n_tiles > 0) {
-        Tile cur = tile_at(0);
-        load_tile(cur);
-        store_tile(0);
         __syncthreads();
-        for (int i = 0; i < n_tiles; ++i) {
-            Tile nxt = cur;
-            const bool more = i + 1 < n_tiles;
-            if (more) {
-                nxt = tile_at(i + 1);
-                load_tile(nxt);
-            }
-            const bool wave_active = wave_has_rows &&
-                (cur.rollout < 0 || (cur.rollout >= wave_n_lo && cur.rollout <= wave_n_hi));
-            if (wave_active) compute_tile(i & 1, cur);
-            if (more) store_tile((i + 1) & 1);
-            __syncthreads();
-            cur = nxt;
-        }
     }
+    const float m_run = m_ref;
 
     // ---- epilogue -------------------------------------------------------------
     const float l_tot = l_run + other_half(l_run);
