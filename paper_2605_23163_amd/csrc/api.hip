@@ -36,6 +36,8 @@ fdd_status check_attn_shape(const fdd_attn_params* p)
     if (p->reserved != 0) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: reserved field must be 0");
     if ((long long)p->N * p->B * (p->Hq / p->Hkv) > (1ll << 30) || (long long)p->N * p->B * p->Hq * p->D > (1ll << 40))
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq too large");
+    if ((long long)p->L * p->Hkv * p->D * 4 >= (1ll << 31))
+        return fail(FDD_ERR_SHAPE, "fdd_block_attn: prefix K (L*Hkv*D elements) must stay below 2 GiB");
     if (std::isnan(p->scale) || std::isinf(p->scale)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: scale is not finite");
     return FDD_OK;
 }
@@ -56,24 +58,50 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
     }
     pl.MT = (pl.R + pl.mtile_rows - 1) / pl.mtile_rows;
     pl.TP = (p.L + pl.key_tile - 1) / pl.key_tile;
-    int s = p.splits;
-    if (s == 0) {
-        // one workgroup per compute unit when the M-tiles alone cannot fill the chip
-        const long long base = (long long)p.Hkv * pl.MT;
-        s = (int)(kNumCU / base);
-        if (s > 64) s = 64;
+    pl.TPU = pl.TP > 0 ? pl.TP : 1;
+    const long long NM = (long long)p.Hkv * pl.MT;
+    pl.U = NM * pl.TPU;
+    bool partials;
+    if (p.dtype == FDD_BF16) {
+        long long w;
+        if (p.splits > 0) {
+            w = NM * (p.splits < pl.TPU ? p.splits : pl.TPU);
+        } else {
+            // one workgroup per compute unit, every one with the same number of
+            // key tiles; tiny problems keep two tiles per workgroup
+            w = pl.U < 2 * kNumCU ? (pl.U + 1) / 2 : kNumCU;
+            if (w > pl.U) w = pl.U;
+        }
+        pl.W = (int)w;
+        pl.splits = 0;
+        const long long upw = pl.U / pl.W;
+        pl.max_seg = (int)((pl.TPU + upw - 1) / upw) + 1;
+        partials = pl.W != NM;
+    } else {
+        int s = p.splits;
+        if (s == 0) {
+            s = (int)(kNumCU / NM);
+            if (s > 64) s = 64;
+        }
+        if (s > pl.TP) s = pl.TP;
+        if (s < 1) s = 1;
+        pl.splits = s;
+        pl.W = 0;
+        pl.max_seg = s;
+        partials = s > 1;
     }
-    if (s > pl.TP) s = pl.TP;
-    if (s < 1) s = 1;
-    pl.splits = s;
-    if (s > 1) {
-        const size_t prow = (size_t)p.Hkv * pl.MT * s * pl.mtile_rows;
+    if (partials) {
+        const size_t prow = (size_t)NM * pl.max_seg * pl.mtile_rows;
         pl.ws_o_bytes = (prow * p.D * sizeof(float) + 255) & ~(size_t)255;
         pl.ws_ml_bytes = (prow * 2 * sizeof(float) + 255) & ~(size_t)255;
     } else {
         pl.ws_o_bytes = 0;
         pl.ws_ml_bytes = 0;
     }
+    // V is repacked once per call when more than one M-tile streams every V tile
+    pl.ws_vt_bytes = 0;
+    if (p.dtype == FDD_BF16 && pl.MT >= 2 && p.L >= pl.key_tile)
+        pl.ws_vt_bytes = (((size_t)p.Hkv * (p.L / pl.key_tile) * pl.key_tile * p.D * 2) + 255) & ~(size_t)255;
     *plan = pl;
     return true;
 }
@@ -89,7 +117,7 @@ size_t fdd_block_attn_workspace(const fdd_attn_params* p)
     if (check_attn_shape(p) != FDD_OK) return 0;
     AttnPlan plan;
     make_attn_plan(*p, &plan);
-    return plan.ws_o_bytes + plan.ws_ml_bytes;
+    return plan.ws_o_bytes + plan.ws_ml_bytes + plan.ws_vt_bytes;
 }
 
 fdd_status fdd_block_attn(const fdd_attn_params* p)
@@ -104,7 +132,7 @@ fdd_status fdd_block_attn(const fdd_attn_params* p)
     if (p->out == p->q) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: out must not alias q");
     AttnPlan plan;
     make_attn_plan(*p, &plan);
-    const size_t need = plan.ws_o_bytes + plan.ws_ml_bytes;
+    const size_t need = plan.ws_o_bytes + plan.ws_ml_bytes + plan.ws_vt_bytes;
     if (need > 0) {
         if (!p->workspace) return fail(FDD_ERR_WORKSPACE, "fdd_block_attn: workspace is NULL, %zu bytes needed", need);
         if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return fail(FDD_ERR_WORKSPACE, "fdd_block_attn: workspace must be 256-byte aligned");
@@ -117,7 +145,7 @@ fdd_status fdd_block_attn(const fdd_attn_params* p)
     hipError_t e = (p->dtype == FDD_BF16) ? launch_attn_bf16(*p, plan, scale, s) : launch_attn_f32(*p, plan, scale, s);
     if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: launch failed: %s", hipGetErrorString(e));
     if (timed && hipEventRecord(g_ev_stop, s) != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: cannot record the stop event");
-    if (plan.splits > 1) {
+    if (plan.ws_o_bytes > 0) {
         e = launch_attn_combine(*p, plan, scale, s);
         if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: merge launch failed: %s", hipGetErrorString(e));
     }

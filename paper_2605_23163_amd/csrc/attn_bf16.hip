@@ -19,13 +19,22 @@
 //     operand of O^T += V^T P^T, so P never leaves the register file and the
 //     accumulator keeps one query row per lane: its rescale is a per-lane
 //     scalar multiply.
-//   * K and V tiles are staged in LDS as they lie in memory, [key][d], with
-//     16-byte stores.  The K fragments of S^T = K Q^T are plain 128-bit reads.
-//     O^T += V^T P^T needs, per lane, 8 keys of one channel: those fragments
-//     come from the gfx950 LDS transpose read (ds_read_b64_tr_b16), which
-//     hands lane i of a 16-lane group column i of a 4 x 16 block, i.e. 4
-//     consecutive keys of channel i.  Row pads (16 bytes for K, 64 for V) make
-//     both kinds of read bank-conflict free.
+//   * O^T += V^T P^T needs, per lane, 8 keys of one channel, i.e. V with the
+//     key index contiguous, while V lies in memory [key][d].  When an M-tile's
+//     keys are streamed by more than one workgroup (R > 256 rows per KV head),
+//     a small pre-pass packs the full prefix tiles of V once into the exact
+//     fragment order, [tile][16-key step][d][half][8 keys], so the main kernel
+//     moves those 16 KB tiles straight from global memory into LDS
+//     (buffer_load ... lds, no registers, no vector ALU work) and reads
+//     fragments as plain conflict-free 128-bit loads.  K tiles take the same
+//     direct path, [key][d] with the 16-byte pieces of a row XOR-swizzled by
+//     the row index, which keeps the K fragment reads conflict-free without
+//     padding.  Otherwise (a single M-tile per head, the ragged last prefix
+//     tile, the in-block tail) tiles are staged through registers as they lie
+//     in memory and V^T fragments come from the gfx950 LDS transpose read
+//     (ds_read_b64_tr_b16: lane i of a 16-lane group receives column i of a
+//     4 x 16 block, i.e. 4 consecutive keys of channel i); row pads of 16
+//     bytes (K) and 64 bytes (V) make both kinds of read conflict-free.
 //   * Full prefix tiles run through a software-pipelined loop written as 32
 //     slots per tile, one per MFMA.  Each slot also carries a slice of vector
 //     ALU work that does not depend on that MFMA: while the matrix pipe
@@ -41,17 +50,24 @@
 //     exceed 1, which fp32 sums and bf16 relative precision do not mind, and
 //     the accumulator rescale becomes a rare wave-uniform branch.  The result
 //     is mathematically the same softmax.
-//   * The prefix is cut into `splits` pieces along L; each piece keeps the
-//     streaming-softmax state (m, l, o) per row and writes it as an fp32
-//     partial that a second small kernel merges (log-sum-exp merge).  With
-//     one piece the kernel normalises and writes bf16 output directly.
+//   * Work is dealt out stream-K style.  The unit of work is one 64-key prefix
+//     tile of one M-tile; all units, ordered by (KV head, M-tile, tile), are
+//     cut into W equal contiguous ranges, one per workgroup, so every compute
+//     unit gets the same amount of work whatever the shape.  A range may end
+//     inside an M-tile and continue in the next one: each such segment keeps
+//     its own streaming-softmax state (m, l, o) per row.  An M-tile that was
+//     covered by a single segment is normalised and written as bf16 output
+//     directly; otherwise the segments leave fp32 partials that a second small
+//     kernel merges (log-sum-exp merge, fixed order).
 //   * A ragged last prefix tile and the in-block tail go through a simpler
 //     masked path: the workgroup stages the block K/V of each rollout its
 //     rows belong to and masks the rows of other rollouts to -inf.
+#include <type_traits>
+
 #include "fdd_internal.h"
 
 namespace fdd {
-namespace {
+namespace attn_bf16 {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
@@ -70,9 +86,26 @@ struct Args {
     uint16_t* out;
     float* ws_o;
     float* ws_ml;
-    int N, B, L, Hq, Hkv, G, R, MT, TP, S;
-    float c;   // scale * log2(e)
+    const uint16_t* vt;   // packed V^T tiles of the full prefix tiles (PACKED kernels only)
+    int N, B, L, Hq, Hkv, G, R, MT, TP;
+    int TPF;        // full prefix tiles = L / 64
+    int TPU;        // units per M-tile = max(TP, 1)
+    int W;          // workgroups
+    int max_seg;    // partial slots per M-tile
+    long long U;    // units in total = Hkv * MT * TPU
+    float c;        // scale * log2(e)
 };
+
+// Segments of M-tile M: the workgroups whose unit range [U w / W, U (w+1) / W)
+// meets [M TPU, (M+1) TPU).
+__host__ __device__ inline int first_wg_of(long long M, const int TPU, const int W, const long long U)
+{
+    return (int)(((M * TPU + 1) * W + U - 1) / U) - 1;
+}
+__host__ __device__ inline int last_wg_of(long long M, const int TPU, const int W, const long long U)
+{
+    return (int)(((M + 1) * TPU * W + U - 1) / U) - 1;
+}
 
 // One 64-key tile of K and V to stream: where it starts, how many of its
 // keys exist, and which rollout's rows may see it (-1: every row).
@@ -94,6 +127,13 @@ struct Cfg {
     static constexpr int K_CHUNKS = KT * (D / 8);        // 16-byte pieces of a K tile
     static constexpr int K_PER_THREAD = K_CHUNKS / THREADS;
     static_assert(K_CHUNKS % THREADS == 0, "tile must divide over the workgroup");
+    // direct-to-LDS path: unpadded 64 x D tiles moved in 1 KB pieces, one per wavefront instruction
+    static constexpr int T_BYTES = KT * D * 2;
+    static constexpr int NI = T_BYTES / 1024 / WAVES;    // pieces per wavefront
+    static constexpr int CH = D / 8;                     // 16-byte pieces per K row
+    static constexpr int RPB = 1024 / (D * 2);           // K rows per 1 KB piece
+    static constexpr int RPL = 256 / (D * 2);            // K rows per 256-byte bank line
+    static_assert(NI >= 1 && T_BYTES % (1024 * WAVES) == 0, "tile must divide over the wavefronts");
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -114,9 +154,10 @@ __device__ __forceinline__ float other_half(float x)
 // the vector work of a slot is not sunk towards its first use.
 #define FDD_PIN(x) asm volatile("" : "+v"(x))
 
-template <int D, int WAVES>
+template <int D, int WAVES, bool PACKED>
 __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
 {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub
     using C = Cfg<D, WAVES>;
     constexpr int KS = D / 16;   // MFMA k-steps of Q K^T
     constexpr int DB = D / 32;   // 32-channel blocks of the output
@@ -129,19 +170,20 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     const int lane = tid & 63;
     const int l32 = lane & 31;
     const int half = lane >> 5;
+    const int lane_linear16 = (l32 * 2 + half) * 16;   // packed V^T: 32 bytes per channel row, 16 per half
 
-    // ---- which (kv head, M-tile, split) this workgroup owns ---------------
-    // Workgroups are dealt to the 8 XCDs round-robin by their linear id.
-    // All M-tiles that stream the same (head, split) piece of the prefix get
-    // ids that are congruent modulo 8, hence the same XCD and the same L2.
-    const int chunks = a.Hkv * a.S;
-    const int xcd = blockIdx.x % kNumXCD;
-    const int seq = blockIdx.x / kNumXCD;
-    const int chunk = (seq / a.MT) * kNumXCD + xcd;
-    const int mt = seq % a.MT;
-    if (chunk >= chunks) return;
-    const int kh = chunk / a.S;
-    const int split = chunk % a.S;
+    // ---- stream-K: this workgroup's contiguous range of (M-tile, prefix tile) units
+    const long long u_end = a.U * (blockIdx.x + 1) / a.W;
+    for (long long u_cur = a.U * blockIdx.x / a.W; u_cur < u_end;) {
+    const int M = (int)(u_cur / a.TPU);              // M-tile index over all KV heads
+    const int t_begin = (int)(u_cur % a.TPU);
+    const int t_end = (int)min((long long)a.TPU, t_begin + (u_end - u_cur));
+    u_cur += t_end - t_begin;
+    const int kh = M / a.MT;
+    const int mt = M % a.MT;
+    const int seg_first = first_wg_of(M, a.TPU, a.W, a.U);
+    const int n_seg = last_wg_of(M, a.TPU, a.W, a.U) - seg_first + 1;
+    const int seg = (int)blockIdx.x - seg_first;
 
     const int BG = a.B * a.G;
     const int row0_wg = mt * MROWS;
@@ -171,11 +213,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     }
 
     // ---- tile schedule -------------------------------------------------------
-    const int t0 = (int)(((long long)split * a.TP) / a.S);
-    const int t1 = (int)(((long long)(split + 1) * a.TP) / a.S);
-    const int n_prefix = t1 - t0;
+    const int t0 = min(t_begin, a.TP);
+    const int n_prefix = min(t_end, a.TP) - t0;
     const int tail_tiles_per_rollout = (a.B + KT - 1) / KT;
-    const int n_tail = (split == a.S - 1) ? (wg_n_hi - wg_n_lo + 1) * tail_tiles_per_rollout : 0;
+    // the segment that ends the M-tile's key range also takes the in-block tail
+    const int n_tail = (t_end == a.TPU) ? (wg_n_hi - wg_n_lo + 1) * tail_tiles_per_rollout : 0;
     const int n_tiles = n_prefix + n_tail;
     const size_t kv_stride = (size_t)a.Hkv * D;       // elements between consecutive keys
 
@@ -316,23 +358,93 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     const uint16_t* pk0 = a.pk + (size_t)t0 * KT * kv_stride + (size_t)kh * D;
     const uint16_t* pv0 = a.pv + (size_t)t0 * KT * kv_stride + (size_t)kh * D;
     const size_t tile_elems = (size_t)KT * kv_stride;
+    // LDS: two K buffers then two V buffers (padded register-staged layout or unpadded direct layout)
+    constexpr int KB_BYTES = PACKED ? C::T_BYTES : C::K_BYTES;
+    constexpr int VB_BYTES = PACKED ? C::T_BYTES : C::V_BYTES;
     unsigned char* const kbuf0 = lds;
-    unsigned char* const vbuf0 = lds + 2 * C::K_BYTES;
+    unsigned char* const vbuf0 = lds + 2 * KB_BYTES;
     bf16x8 p[4];      // probabilities of a tile as MFMA B operands, one per 16-key step
+
+    // direct path: per-lane byte offsets of the pieces this lane moves, and of
+    // the fragments it reads
+    typedef __attribute__((address_space(3))) void lds_void;
+    __amdgpu_buffer_rsrc_t k_rsrc, v_rsrc;
+    uint32_t k_voff[C::NI], v_voff[C::NI], k_fragoff[KS];
+    if (PACKED) {
+        k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.pk), 0, a.L * a.Hkv * D * 2, 0x00020000);
+        v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.vt), 0, a.Hkv * a.TPF * C::T_BYTES, 0x00020000);
+#pragma unroll
+        for (int j = 0; j < C::NI; ++j) {
+            const int piece = wave * C::NI + j;
+            const int r = piece * C::RPB + lane / C::CH;          // key row of this lane's 16 bytes
+            const int c = (lane % C::CH) ^ ((r / C::RPL) & (C::CH - 1));   // which piece of the row lands here
+            k_voff[j] = (uint32_t)(r * (int)kv_stride * 2 + c * 16);
+            v_voff[j] = (uint32_t)(piece * 1024 + lane * 16);
+        }
+        const int y = ((l32 / C::RPL) & (C::CH - 1)) ^ half;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) k_fragoff[ks] = (uint32_t)(l32 * D * 2 + (((2 * ks) ^ y) << 4));
+    }
+    // start moving prefix tile `t` (index inside this segment) into buffer `buf`
+    auto fetch_k = [&](int t, int buf) {
+        if (PACKED) {
+            const uint32_t soff = (uint32_t)(((size_t)(t0 + t) * KT * kv_stride + (size_t)kh * D) * 2);
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lds_void*)(kbuf0 + buf * KB_BYTES + (wave * C::NI + j) * 1024),
+                                                         16, k_voff[j], soff, 0, 0);
+        } else {
+            load_k(pk0 + (size_t)t * tile_elems, KT, true);
+        }
+    };
+    auto fetch_v = [&](int t, int buf) {
+        if (PACKED) {
+            const uint32_t soff = (uint32_t)(((size_t)kh * a.TPF + (t0 + t)) * C::T_BYTES);
+#pragma unroll
+            for (int j = 0; j < C::NI; ++j)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lds_void*)(vbuf0 + buf * VB_BYTES + (wave * C::NI + j) * 1024),
+                                                         16, v_voff[j], soff, 0, 0);
+        } else {
+            load_v(pv0 + (size_t)t * tile_elems, KT, true);
+        }
+    };
+    // make the fetched tiles visible to the workgroup
+    auto publish = [&]() {
+        if (PACKED) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct loads have landed
+        __syncthreads();
+    };
+    // fragments of the fast path.  K: key block kb (32 keys), k-step ks.
+    auto k_frag_fast = [&](int buf, int kb, int ks) -> bf16x8 {
+        if (PACKED) return *reinterpret_cast<const bf16x8*>(kbuf0 + buf * KB_BYTES + kb * 32 * D * 2 + k_fragoff[ks]);
+        return *reinterpret_cast<const bf16x8*>(kbuf0 + buf * KB_BYTES + (kb * 32 + l32) * C::KROW + ks * 32 + half * 16);
+    };
+    // V^T: 16-key step t4, channel block db
+    auto v_frag_fast = [&](int buf, int t4, int db) -> bf16x8 {
+        if (PACKED) return *reinterpret_cast<const bf16x8*>(vbuf0 + buf * VB_BYTES + t4 * (D * 32) + db * 1024 + lane_linear16);
+        return v_frag(vbuf0 + buf * VB_BYTES, t4, db);
+    };
 
     if (F > 0) {
         // prologue: K(0), V(0) and K(1) into LDS, scores of tile 0
-        load_k(pk0, KT, true);
-        load_v(pv0, KT, true);
-        store_k(0);
-        store_v(0);
-        load_k(pk0 + (size_t)min(1, F - 1) * tile_elems, KT, true);
-        store_k(1);
-        __syncthreads();
+        fetch_k(0, 0);
+        fetch_v(0, 0);
+        if (!PACKED) {
+            store_k(0);
+            store_v(0);
+        }
+        fetch_k(min(1, F - 1), 1);
+        if (!PACKED) store_k(1);
+        publish();
         f32x16 sa[2], sb[2];
-        qk_block(kbuf0, 0, sa[0]);
-        qk_block(kbuf0, 1, sa[1]);
-        __syncthreads();   // K buffer 0 is overwritten at the end of the first step
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sa[kb][v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                sa[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag_fast(0, kb, ks), qf[ks], sa[kb], 0, 0, 0);
+        }
+        __syncthreads();   // K buffer 0 is refilled during the first step
 
         // One pipelined step: probabilities and P V of tile i from s_cur while
         // the scores of tile i+1 go to s_nxt; K(i+2) and V(i+1) are fetched.
@@ -340,16 +452,17 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         //   slots  8-15  S(i+1) second 32 keys  ||  exp of the first 32 keys
         //   slots 16-23  P V first 32 keys      ||  exp of the second 32 keys
         //   slots 24-31  P V second 32 keys     ||  staging of the fetched tiles
-        auto step = [&](int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2], bool has_next) {
-            load_k(pk0 + (size_t)min(i + 2, F - 1) * tile_elems, KT, true);
-            load_v(pv0 + (size_t)min(i + 1, F - 1) * tile_elems, KT, true);
-            const unsigned char* kl = kbuf0 + ((i + 1) & 1) * C::K_BYTES + l32 * C::KROW + half * 16;
-            const unsigned char* vl = vbuf0 + (i & 1) * C::V_BYTES;
-            auto kfrag = [&](int kb, int ks) {
-                return *reinterpret_cast<const bf16x8*>(kl + kb * 32 * C::KROW + ks * 32);
-            };
+        // `par` is i % 2 as a compile-time constant (buffer offsets become
+        // immediates), `nxt` says whether tile i+1 exists.
+        auto step = [&](auto par, auto nxt, int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2]) {
+            constexpr int P = decltype(par)::value;
+            constexpr bool has_next = decltype(nxt)::value;
+            // the buffers refilled here were last read in the previous step
+            fetch_k(min(i + 2, F - 1), P);
+            fetch_v(min(i + 1, F - 1), 1 - P);
+            auto kfrag = [&](int kb, int ks) { return k_frag_fast(1 - P, kb, ks); };
             // P V slot j of block kb: 16-key step j / DB, channel block j % DB
-            auto vfrag = [&](int kb, int j) { return v_frag(vl, kb * 2 + j / DB, j % DB); };
+            auto vfrag = [&](int kb, int j) { return v_frag_fast(P, kb * 2 + j / DB, j % DB); };
             bf16x8 f[3];
             FDD_SCHED_FENCE();
 
@@ -430,29 +543,36 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             p[3] = __builtin_bit_cast(bf16x8, pw[3]);
             l_run += acc;
 
-            // ---- slots 24-31 ---- (the buffers written here were last read in the previous step)
+            // ---- slots 24-31 ----
             f[0] = vfrag(1, 0);
             f[1] = vfrag(1, 1);
 #pragma unroll
             for (int j = 0; j < PVS; ++j) {
                 if (j + 2 < PVS) f[(j + 2) % 3] = vfrag(1, j + 2);
                 o[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], p[2 + j / DB], o[j % DB], 0, 0, 0);
-                if (j == 1) store_k(i & 1);
-                if (j == PVS / 2 + 1) store_v((i + 1) & 1);
+                if (!PACKED) {
+                    if (j == 1) store_k(P);
+                    if (j == PVS / 2 + 1) store_v(1 - P);
+                }
                 FDD_SCHED_FENCE();
             }
-            __syncthreads();
+            publish();
         };
+        using std::integral_constant;
+        const integral_constant<int, 0> even;
+        const integral_constant<int, 1> odd;
+        const integral_constant<bool, true> more;
+        const integral_constant<bool, false> last;
         int i = 0;
         for (; i + 2 < F; i += 2) {
-            step(i, sa, sb, true);
-            step(i + 1, sb, sa, true);
+            step(even, more, i, sa, sb);
+            step(odd, more, i + 1, sb, sa);
         }
         if (i + 2 == F) {
-            step(i, sa, sb, true);
-            step(i + 1, sb, sa, false);
+            step(even, more, i, sa, sb);
+            step(odd, last, i + 1, sb, sa);
         } else {
-            step(i, sa, sb, false);
+            step(even, last, i, sa, sb);
         }
     }
     f32x16 s[2];      // scores of a masked tile
@@ -462,14 +582,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const Tile t = tile_at(i);
         load_k(t.k, t.valid, false);
         load_v(t.v, t.valid, false);
-        store_k(0);
-        store_v(0);
+        store_rows(kreg, lds, C::KROW);
+        store_rows(vreg, lds + C::K_BYTES, C::VROW);
         __syncthreads();
         const bool wave_active = wave_has_rows &&
             (t.rollout < 0 || (t.rollout >= wave_n_lo && t.rollout <= wave_n_hi));
         if (wave_active) {
-            qk_block(kbuf0, 0, s[0]);
-            qk_block(kbuf0, 1, s[1]);
+            qk_block(lds, 0, s[0]);
+            qk_block(lds, 1, s[1]);
             // register v of block kb is key kb*32 + (v/4)*8 + half*4 + v%4
             const bool row_sees = (t.rollout < 0) || (t.rollout == my_rollout);
 #pragma unroll
@@ -483,57 +603,98 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             const float mc = ((m_ref == -INFINITY) ? 0.f : m_ref) * a.c;
             exp_block(s[0], mc, p[0], p[1]);
             exp_block(s[1], mc, p[2], p[3]);
-            pv_block(vbuf0, 0, p[0], p[1]);
-            pv_block(vbuf0, 1, p[2], p[3]);
+            pv_block(lds + C::K_BYTES, 0, p[0], p[1]);
+            pv_block(lds + C::K_BYTES, 1, p[2], p[3]);
         }
         __syncthreads();
     }
     const float m_run = m_ref;
 
-    // ---- epilogue -------------------------------------------------------------
+    // ---- epilogue of the segment ------------------------------------------------
     const float l_tot = l_run + other_half(l_run);
-    if (!row_ok) return;
-    if (a.S == 1) {
-        const float inv = 1.f / l_tot;
-        uint16_t* op = a.out + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D;
+    if (row_ok) {
+        if (n_seg == 1) {
+            const float inv = 1.f / l_tot;
+            uint16_t* op = a.out + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+            for (int db = 0; db < DB; ++db)
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int d = db * 32 + v4 * 8 + half * 4;
-                typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-                bf16x4 w;
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const int d = db * 32 + v4 * 8 + half * 4;
+                    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+                    bf16x4 w;
 #pragma unroll
-                for (int j = 0; j < 4; ++j) w[j] = (__bf16)(o[db][v4 * 4 + j] * inv);
-                *reinterpret_cast<bf16x4*>(op + d) = w;
+                    for (int j = 0; j < 4; ++j) w[j] = (__bf16)(o[db][v4 * 4 + j] * inv);
+                    *reinterpret_cast<bf16x4*>(op + d) = w;
+                }
+        } else {
+            const size_t prow = ((size_t)M * a.max_seg + seg) * MROWS + (wave * 32 + l32);
+            float* wo = a.ws_o + prow * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int v4 = 0; v4 < 4; ++v4) {
+                    const int d = db * 32 + v4 * 8 + half * 4;
+                    float4 w = make_float4(o[db][v4 * 4 + 0], o[db][v4 * 4 + 1], o[db][v4 * 4 + 2], o[db][v4 * 4 + 3]);
+                    *reinterpret_cast<float4*>(wo + d) = w;
+                }
+            if (half == 0) {
+                a.ws_ml[prow * 2 + 0] = m_run;
+                a.ws_ml[prow * 2 + 1] = l_tot;
             }
-    } else {
-        const size_t prow = (((size_t)kh * a.MT + mt) * a.S + split) * MROWS + (wave * 32 + l32);
-        float* wo = a.ws_o + prow * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int d = db * 32 + v4 * 8 + half * 4;
-                float4 w = make_float4(o[db][v4 * 4 + 0], o[db][v4 * 4 + 1], o[db][v4 * 4 + 2], o[db][v4 * 4 + 3]);
-                *reinterpret_cast<float4*>(wo + d) = w;
-            }
-        if (half == 0) {
-            a.ws_ml[prow * 2 + 0] = m_run;
-            a.ws_ml[prow * 2 + 1] = l_tot;
         }
+    }
+    }   // next segment of this workgroup's range
+#endif
+}
+
+// ---------------------------------------------------------------------------
+// Pre-pass: the full 64-key prefix tiles of V, repacked once into the order
+// the P V fragments are read in:  vt[kh][tile][t4][d][half][8 keys], where the
+// 8 keys of (t4, half) are 16 t4 + 4 half + {0..3} and 16 t4 + 8 + 4 half + {0..3}
+// (the key order of the probabilities in the S^T accumulator).  One workgroup
+// per (tile, KV head): stage the tile [key][d] in LDS, then let the LDS
+// transpose read do the transposition; every wavefront store is 2 KB contiguous.
+template <int D>
+__global__ __launch_bounds__(512) void vt_pack_kernel(const uint16_t* __restrict__ pv, uint16_t* __restrict__ vt,
+                                                       int Hkv, int TPF)
+{
+    using C = Cfg<D, 8>;
+    constexpr int DB = D / 32;
+    __shared__ __align__(16) unsigned char tile[C::V_BYTES];
+    const int t = blockIdx.x, kh = blockIdx.y;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
+    const size_t kv_stride = (size_t)Hkv * D;
+    const uint16_t* src = pv + (size_t)t * KT * kv_stride + (size_t)kh * D;
+#pragma unroll
+    for (int i = 0; i < C::K_PER_THREAD; ++i) {
+        const int c = tid + i * C::THREADS;
+        const int key = c / (D / 8), col = c % (D / 8);
+        *reinterpret_cast<u32x4*>(tile + key * C::VROW + col * 16) =
+            *reinterpret_cast<const u32x4*>(src + (size_t)key * kv_stride + col * 8);
+    }
+    __syncthreads();
+    const int tr_lane_off = ((half * 4 + ((lane & 15) >> 2)) * C::VROW) + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+    unsigned char* dst = reinterpret_cast<unsigned char*>(vt) + ((size_t)kh * TPF + t) * C::T_BYTES;
+    for (int combo = wave; combo < 4 * DB; combo += 8) {
+        const int t4 = combo / DB, db = combo % DB;
+        typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+        const unsigned char* p0 = tile + tr_lane_off + (t4 * 16) * C::VROW + db * 64;
+        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0));
+        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0 + 8 * C::VROW));
+        typedef short i16x8 __attribute__((ext_vector_type(8)));
+        const i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        *reinterpret_cast<i16x8*>(dst + t4 * (D * 32) + (db * 32 + l32) * 32 + half * 16) = both;
     }
 }
 
-template <int D, int WAVES>
+template <int D, int WAVES, bool PACKED>
 hipError_t launch(const Args& a, hipStream_t stream)
 {
     using C = Cfg<D, WAVES>;
-    const int chunks = a.Hkv * a.S;
-    const int chunk_groups = (chunks + kNumXCD - 1) / kNumXCD;
-    const int grid = chunk_groups * a.MT * kNumXCD;
-    const size_t lds_bytes = 2 * (size_t)C::BUF_BYTES;
-    auto kern = attn_bf16_kernel<D, WAVES>;
+    const size_t lds_bytes = PACKED ? 4 * (size_t)C::T_BYTES : 2 * (size_t)C::BUF_BYTES;
+    static_assert(4 * C::T_BYTES >= C::BUF_BYTES, "the masked path stages one padded K and V tile");
+    const auto kern = &attn_bf16_kernel<D, WAVES, PACKED>;
     static bool attr_done = false;   // per instantiation
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -541,11 +702,19 @@ hipError_t launch(const Args& a, hipStream_t stream)
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::THREADS), lds_bytes, stream, a);
+    if (PACKED) {
+        hipLaunchKernelGGL(vt_pack_kernel<D>, dim3(a.TPF, a.Hkv), dim3(512), 0, stream, a.pv, const_cast<uint16_t*>(a.vt),
+                           a.Hkv, a.TPF);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kern, dim3(a.W), dim3(C::THREADS), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
-}  // namespace
+}  // namespace attn_bf16
+
+using namespace attn_bf16;
 
 hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s)
 {
@@ -556,13 +725,18 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.bk = static_cast<const uint16_t*>(p.block_k);
     a.bv = static_cast<const uint16_t*>(p.block_v);
     a.out = static_cast<uint16_t*>(p.out);
-    a.ws_o = static_cast<float*>(p.workspace);
-    a.ws_ml = reinterpret_cast<float*>(static_cast<char*>(p.workspace) + plan.ws_o_bytes);
+    char* ws = static_cast<char*>(p.workspace);
+    a.ws_o = reinterpret_cast<float*>(ws);
+    a.ws_ml = reinterpret_cast<float*>(ws + plan.ws_o_bytes);
+    a.vt = reinterpret_cast<const uint16_t*>(ws + plan.ws_o_bytes + plan.ws_ml_bytes);
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
-    a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.S = plan.splits;
+    a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.TPF = p.L / 64;
+    a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.U = plan.U;
     a.c = scale * 1.4426950408889634f;
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;
-    return p.D == 128 ? launch<128, 8>(a, s) : launch<64, 8>(a, s);
+    if (plan.ws_vt_bytes > 0)
+        return p.D == 128 ? launch<128, 8, true>(a, s) : launch<64, 8, true>(a, s);
+    return p.D == 128 ? launch<128, 8, false>(a, s) : launch<64, 8, false>(a, s);
 }
 
 }  // namespace fdd

@@ -177,14 +177,18 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
 }
 
 // ---------------------------------------------------------------------------
-// Merge of the per-split partials (log-sum-exp merge), for both storage types:
+// Merge of the per-segment partials (log-sum-exp merge), for both storage types:
 //   m* = max_s m_s,  w_s = 2^((m_s - m*) c),  out = sum_s w_s o_s / sum_s w_s l_s
 // The sum runs over s in a fixed order, so results are reproducible.
 struct CombineArgs {
     const float* ws_o;
     const float* ws_ml;
     void* out;
-    int B, Hq, Hkv, G, R, MT, S, mrows, D, bf16;
+    int B, Hq, Hkv, G, R, MT, mrows, D, bf16;
+    int max_seg;     // slots per M-tile in the workspace
+    int fixed_seg;   // > 0: every M-tile has this many segments; 0: stream-K ranges
+    int TPU, W;
+    long long U;
     float c;
 };
 
@@ -199,12 +203,21 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(CombineArgs a)
     const int row = (int)(hr % a.R);
     const int kh = (int)(hr / a.R);
     const int mt = row / a.mrows, rit = row % a.mrows;
-    const size_t p0 = (((size_t)kh * a.MT + mt) * a.S) * a.mrows + rit;
+    const long long M = (long long)kh * a.MT + mt;
+    int n_seg = a.fixed_seg;
+    if (n_seg == 0) {
+        // same arithmetic as the attention kernel: workgroups whose unit range meets this M-tile
+        const int first = (int)(((M * a.TPU + 1) * a.W + a.U - 1) / a.U) - 1;
+        const int last = (int)(((M + 1) * a.TPU * a.W + a.U - 1) / a.U) - 1;
+        n_seg = last - first + 1;
+        if (n_seg == 1) return;     // written in final form by its only segment
+    }
+    const size_t p0 = ((size_t)M * a.max_seg) * a.mrows + rit;
     float mstar = -INFINITY;
-    for (int s = 0; s < a.S; ++s) mstar = fmaxf(mstar, a.ws_ml[(p0 + (size_t)s * a.mrows) * 2]);
+    for (int s = 0; s < n_seg; ++s) mstar = fmaxf(mstar, a.ws_ml[(p0 + (size_t)s * a.mrows) * 2]);
     float l = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < a.S; ++s) {
+    for (int s = 0; s < n_seg; ++s) {
         const size_t pr = p0 + (size_t)s * a.mrows;
         const float w = exp2f((a.ws_ml[pr * 2] - mstar) * a.c);
         l = fmaf(a.ws_ml[pr * 2 + 1], w, l);
@@ -261,7 +274,9 @@ hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, f
     a.ws_ml = reinterpret_cast<const float*>(static_cast<const char*>(p.workspace) + plan.ws_o_bytes);
     a.out = p.out;
     a.B = p.B; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = plan.G; a.R = plan.R; a.MT = plan.MT;
-    a.S = plan.splits; a.mrows = plan.mtile_rows; a.D = p.D; a.bf16 = (p.dtype == FDD_BF16);
+    a.mrows = plan.mtile_rows; a.D = p.D; a.bf16 = (p.dtype == FDD_BF16);
+    a.max_seg = plan.max_seg; a.fixed_seg = a.bf16 ? 0 : plan.splits;
+    a.TPU = plan.TPU; a.W = plan.W; a.U = plan.U;
     a.c = scale * 1.4426950408889634f;
     const long long total = (long long)p.Hkv * plan.R * (p.D / 4);
     const int grid = (int)((total + 255) / 256);

