@@ -170,9 +170,10 @@ fdd_status fdd_block_kv_update(const fdd_kv_update_params *p);
 /* ------------------------------------------------------------------------
  * Timing hook for benchmarks.  While set (both non-NULL), every
  * fdd_block_attn call made by this host thread records `start` on the call's
- * stream right before the main attention kernel and `stop` right after it
- * (before the small merge kernel), so hipEventElapsedTime(start, stop) is
- * that kernel's duration.  Both are hipEvent_t passed as void*, owned by the
+ * stream right before the main attention kernel (after the pre-pass that
+ * repacks V, when there is one) and `stop` right after it (before the small
+ * merge kernel), so hipEventElapsedTime(start, stop) is that kernel's
+ * duration.  Both are hipEvent_t passed as void*, owned by the
  * caller.  Pass NULL, NULL to clear.  Not meant for production loops.
  */
 fdd_status fdd_profile_attn_events(void *start, void *stop);

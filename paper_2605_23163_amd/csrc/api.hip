@@ -141,8 +141,13 @@ fdd_status fdd_block_attn(const fdd_attn_params* p)
     const float scale = p->scale > 0.f ? p->scale : 1.f / std::sqrt((float)p->D);
     hipStream_t s = static_cast<hipStream_t>(p->stream);
     const bool timed = g_ev_start && g_ev_stop;
-    if (timed && hipEventRecord(g_ev_start, s) != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: cannot record the start event");
-    hipError_t e = (p->dtype == FDD_BF16) ? launch_attn_bf16(*p, plan, scale, s) : launch_attn_f32(*p, plan, scale, s);
+    hipError_t e;
+    if (p->dtype == FDD_BF16) {
+        e = launch_attn_bf16(*p, plan, scale, s, timed ? g_ev_start : nullptr);
+    } else {
+        if (timed && hipEventRecord(g_ev_start, s) != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: cannot record the start event");
+        e = launch_attn_f32(*p, plan, scale, s);
+    }
     if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: launch failed: %s", hipGetErrorString(e));
     if (timed && hipEventRecord(g_ev_stop, s) != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: cannot record the stop event");
     if (plan.ws_o_bytes > 0) {

@@ -23,7 +23,7 @@
 //     key index contiguous, while V lies in memory [key][d].  When an M-tile's
 //     keys are streamed by more than one workgroup (R > 256 rows per KV head),
 //     a small pre-pass packs the full prefix tiles of V once into the exact
-//     fragment order, [tile][16-key step][d][half][8 keys], so the main kernel
+//     fragment order, [tile][16-key step][half][d][8 keys], so the main kernel
 //     moves those 16 KB tiles straight from global memory into LDS
 //     (buffer_load ... lds, no registers, no vector ALU work) and reads
 //     fragments as plain conflict-free 128-bit loads.  K tiles take the same
@@ -170,11 +170,16 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     const int lane = tid & 63;
     const int l32 = lane & 31;
     const int half = lane >> 5;
-    const int lane_linear16 = (l32 * 2 + half) * 16;   // packed V^T: 32 bytes per channel row, 16 per half
 
     // ---- stream-K: this workgroup's contiguous range of (M-tile, prefix tile) units
-    const long long u_end = a.U * (blockIdx.x + 1) / a.W;
-    for (long long u_cur = a.U * blockIdx.x / a.W; u_cur < u_end;) {
+    // Workgroups are dealt to the 8 XCDs round-robin by their launch index.
+    // Ranges are numbered so that the workgroups of one XCD own neighbouring
+    // ranges: they stream the K/V of the same KV head a few tiles apart, and the
+    // XCD's L2 serves all but the first of them.
+    const int wg = (a.W % kNumXCD == 0) ? (int)(blockIdx.x % kNumXCD) * (a.W / kNumXCD) + (int)(blockIdx.x / kNumXCD)
+                                        : (int)blockIdx.x;
+    const long long u_end = a.U * (wg + 1) / a.W;
+    for (long long u_cur = a.U * wg / a.W; u_cur < u_end;) {
     const int M = (int)(u_cur / a.TPU);              // M-tile index over all KV heads
     const int t_begin = (int)(u_cur % a.TPU);
     const int t_end = (int)min((long long)a.TPU, t_begin + (u_end - u_cur));
@@ -183,7 +188,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     const int mt = M % a.MT;
     const int seg_first = first_wg_of(M, a.TPU, a.W, a.U);
     const int n_seg = last_wg_of(M, a.TPU, a.W, a.U) - seg_first + 1;
-    const int seg = (int)blockIdx.x - seg_first;
+    const int seg = wg - seg_first;
 
     const int BG = a.B * a.G;
     const int row0_wg = mt * MROWS;
@@ -370,6 +375,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     typedef __attribute__((address_space(3))) void lds_void;
     __amdgpu_buffer_rsrc_t k_rsrc, v_rsrc;
     uint32_t k_voff[C::NI], v_voff[C::NI], k_fragoff[KS];
+    const uint32_t v_fragoff = (uint32_t)(half * (D * 16) + l32 * 16);   // packed V^T: [16-key step][half][d][8 keys]
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // same value, known to be wave-uniform
     if (PACKED) {
         k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.pk), 0, a.L * a.Hkv * D * 2, 0x00020000);
         v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.vt), 0, a.Hkv * a.TPF * C::T_BYTES, 0x00020000);
@@ -388,10 +395,10 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     // start moving prefix tile `t` (index inside this segment) into buffer `buf`
     auto fetch_k = [&](int t, int buf) {
         if (PACKED) {
-            const uint32_t soff = (uint32_t)(((size_t)(t0 + t) * KT * kv_stride + (size_t)kh * D) * 2);
+            const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)(((size_t)(t0 + t) * KT * kv_stride + (size_t)kh * D) * 2));
 #pragma unroll
             for (int j = 0; j < C::NI; ++j)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lds_void*)(kbuf0 + buf * KB_BYTES + (wave * C::NI + j) * 1024),
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lds_void*)(kbuf0 + buf * KB_BYTES + (wave_u * C::NI + j) * 1024),
                                                          16, k_voff[j], soff, 0, 0);
         } else {
             load_k(pk0 + (size_t)t * tile_elems, KT, true);
@@ -399,10 +406,10 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     };
     auto fetch_v = [&](int t, int buf) {
         if (PACKED) {
-            const uint32_t soff = (uint32_t)(((size_t)kh * a.TPF + (t0 + t)) * C::T_BYTES);
+            const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)(((size_t)kh * a.TPF + (t0 + t)) * C::T_BYTES));
 #pragma unroll
             for (int j = 0; j < C::NI; ++j)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lds_void*)(vbuf0 + buf * VB_BYTES + (wave * C::NI + j) * 1024),
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lds_void*)(vbuf0 + buf * VB_BYTES + (wave_u * C::NI + j) * 1024),
                                                          16, v_voff[j], soff, 0, 0);
         } else {
             load_v(pv0 + (size_t)t * tile_elems, KT, true);
@@ -420,7 +427,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     };
     // V^T: 16-key step t4, channel block db
     auto v_frag_fast = [&](int buf, int t4, int db) -> bf16x8 {
-        if (PACKED) return *reinterpret_cast<const bf16x8*>(vbuf0 + buf * VB_BYTES + t4 * (D * 32) + db * 1024 + lane_linear16);
+        if (PACKED) return *reinterpret_cast<const bf16x8*>(vbuf0 + buf * VB_BYTES + t4 * (D * 32) + db * 512 + v_fragoff);
         return v_frag(vbuf0 + buf * VB_BYTES, t4, db);
     };
 
@@ -650,11 +657,11 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
 
 // ---------------------------------------------------------------------------
 // Pre-pass: the full 64-key prefix tiles of V, repacked once into the order
-// the P V fragments are read in:  vt[kh][tile][t4][d][half][8 keys], where the
+// the P V fragments are read in:  vt[kh][tile][t4][half][d][8 keys], where the
 // 8 keys of (t4, half) are 16 t4 + 4 half + {0..3} and 16 t4 + 8 + 4 half + {0..3}
 // (the key order of the probabilities in the S^T accumulator).  One workgroup
 // per (tile, KV head): stage the tile [key][d] in LDS, then let the LDS
-// transpose read do the transposition; every wavefront store is 2 KB contiguous.
+// transpose read do the transposition; a wavefront stores two 512-byte runs.
 template <int D>
 __global__ __launch_bounds__(512) void vt_pack_kernel(const uint16_t* __restrict__ pv, uint16_t* __restrict__ vt,
                                                        int Hkv, int TPF)
@@ -684,12 +691,12 @@ __global__ __launch_bounds__(512) void vt_pack_kernel(const uint16_t* __restrict
         const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0 + 8 * C::VROW));
         typedef short i16x8 __attribute__((ext_vector_type(8)));
         const i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        *reinterpret_cast<i16x8*>(dst + t4 * (D * 32) + (db * 32 + l32) * 32 + half * 16) = both;
+        *reinterpret_cast<i16x8*>(dst + t4 * (D * 32) + half * (D * 16) + (db * 32 + l32) * 16) = both;
     }
 }
 
 template <int D, int WAVES, bool PACKED>
-hipError_t launch(const Args& a, hipStream_t stream)
+hipError_t launch(const Args& a, hipStream_t stream, hipEvent_t before_main)
 {
     using C = Cfg<D, WAVES>;
     const size_t lds_bytes = PACKED ? 4 * (size_t)C::T_BYTES : 2 * (size_t)C::BUF_BYTES;
@@ -708,6 +715,10 @@ hipError_t launch(const Args& a, hipStream_t stream)
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
+    if (before_main) {
+        hipError_t e = hipEventRecord(before_main, stream);
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(kern, dim3(a.W), dim3(C::THREADS), lds_bytes, stream, a);
     return hipGetLastError();
 }
@@ -716,7 +727,7 @@ hipError_t launch(const Args& a, hipStream_t stream)
 
 using namespace attn_bf16;
 
-hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s)
+hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s, hipEvent_t before_main)
 {
     Args a;
     a.q = static_cast<const uint16_t*>(p.q);
@@ -735,8 +746,8 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.c = scale * 1.4426950408889634f;
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;
     if (plan.ws_vt_bytes > 0)
-        return p.D == 128 ? launch<128, 8, true>(a, s) : launch<64, 8, true>(a, s);
-    return p.D == 128 ? launch<128, 8, false>(a, s) : launch<64, 8, false>(a, s);
+        return p.D == 128 ? launch<128, 8, true>(a, s, before_main) : launch<64, 8, true>(a, s, before_main);
+    return p.D == 128 ? launch<128, 8, false>(a, s, before_main) : launch<64, 8, false>(a, s, before_main);
 }
 
 }  // namespace fdd

@@ -45,7 +45,8 @@ struct AttnPlan {
 
 bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan);
 
-hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);
+// `before_main`, if not null, is recorded on the stream right before the main kernel (after the V pre-pass).
+hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s, hipEvent_t before_main);
 hipError_t launch_attn_f32(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);
 hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);
 
