@@ -7,7 +7,8 @@ A "step" is one pass of the whole hot path over one batch of synthetic
 input that is already resident in HBM: shared-prefix block attention,
 confidence-threshold unmask over the vocabulary, and the K/V refresh of the
 committed positions; every 8 steps the N rollouts are re-forked from one
-parent block state (a new block starts), which is the fork bookkeeping.
+parent block state (a new block starts), which is the fork bookkeeping, and
+the prefix V is laid out once for the attention kernel (fdd_prefix_pack).
 The default workload is the long multi-camera configuration (N=16 rollouts,
 B=64, prefix L=16384, V=152064, bf16).
 
@@ -182,8 +183,10 @@ def main():
     conf = torch.empty((w.N, w.B), dtype=torch.float32, device="cuda")
     nun = torch.empty((w.N,), dtype=torch.int32, device="cuda")
     com = torch.empty((w.N, w.B), dtype=torch.uint8, device="cuda")
+    packed_v = torch.empty(max(256, F.fdd_prefix_pack_bytes(g["prefix_v"])), dtype=torch.uint8, device="cuda")
     ws_a = torch.empty(max(256, F.fdd_block_attn_workspace(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"],
-                                                           st["block_v"])), dtype=torch.uint8, device="cuda")
+                                                           st["block_v"], prefix_v_packed=packed_v)),
+                       dtype=torch.uint8, device="cuda")
     ws_u = torch.empty(max(256, F.fdd_unmask_workspace(logits[0]) if has_unmask else 256), dtype=torch.uint8,
                        device="cuda")
     tau = float(np.float32(w.tau))
@@ -196,10 +199,12 @@ def main():
         if timed:
             F.fdd_profile_attn_events(*ev.pairs[i])
         if i % STEPS_PER_BLOCK == 0:
+            # a new block: fork the rollouts and lay the (unchanged) prefix V out for the kernel once
             for k in parent:
                 F.fdd_fork_block(parent[k], w.N, dst=st[k])
+            F.fdd_prefix_pack(g["prefix_v"], packed=packed_v)
         F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"], scaffold, out=out,
-                         workspace=ws_a)
+                         workspace=ws_a, prefix_v_packed=packed_v)
         if has_unmask:
             if timed:
                 un0[i].record()

@@ -92,12 +92,36 @@ typedef struct fdd_attn_params {
     void *stream;                  /* hipStream_t */
     int32_t splits;                /* 0 = automatic */
     int32_t reserved;              /* must be 0 */
+    const void *prefix_v_packed;   /* optional: output of fdd_prefix_pack for this prefix_v, or NULL */
 } fdd_attn_params;
 
 /* Bytes of scratch fdd_block_attn needs for these params (host-only
- * arithmetic, no device is touched).  Returns 0 if the params are invalid. */
+ * arithmetic, no device is touched).  Returns 0 if the params are invalid.
+ * The figure is smaller when prefix_v_packed is set. */
 size_t fdd_block_attn_workspace(const fdd_attn_params *p);
 fdd_status fdd_block_attn(const fdd_attn_params *p);
+
+/* ------------------------------------------------------------------------
+ * fdd_prefix_pack: one-time relayout of the prefix V for the bf16 kernel.
+ *
+ * The prefix KV cache does not change while a block is denoised and is shared
+ * by all rollouts (paper: KV caches of the prompt and of earlier blocks are
+ * reused without recomputation).  The bf16 attention kernel reads the full
+ * 64-key tiles of prefix V in an order that has the key index contiguous;
+ * when several workgroups stream the same V, fdd_block_attn repacks V into
+ * its workspace on every call.  A caller that runs many steps on one prefix
+ * can do that once: fdd_prefix_pack writes the repacked copy (a few percent
+ * of a step's time) and every later fdd_block_attn on the same prefix takes
+ * it through prefix_v_packed.  prefix_v itself must still be passed (the
+ * ragged last tile is read from it).  The packed copy belongs to exactly the
+ * (prefix_v contents, L, Hkv, D) it was made from.
+ *
+ * fdd_prefix_pack_bytes: size of the packed copy, 256-byte granular; 0 when
+ * nothing would be packed (fp32, or L < 64).  Host-only arithmetic.
+ */
+size_t fdd_prefix_pack_bytes(int32_t L, int32_t Hkv, int32_t D, int32_t dtype);
+fdd_status fdd_prefix_pack(const void *prefix_v, int32_t L, int32_t Hkv, int32_t D, int32_t dtype,
+                           void *packed, size_t packed_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
  * fdd_unmask_step: one confidence-threshold unmask iteration over N blocks.

@@ -12,6 +12,8 @@ from .binding import (  # noqa: F401
     fdd_block_kv_update,
     fdd_fork_block,
     fdd_last_error,
+    fdd_prefix_pack,
+    fdd_prefix_pack_bytes,
     fdd_profile_attn_events,
     fdd_unmask_step,
     fdd_unmask_workspace,

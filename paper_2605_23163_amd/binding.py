@@ -14,7 +14,8 @@ _LIB_PATH = os.path.join(_HERE, "libfdd.so")
 _lib = None
 
 FDD_F32, FDD_BF16 = 0, 1
-EXPORTS = ("fdd_block_attn_workspace", "fdd_block_attn", "fdd_unmask_workspace", "fdd_unmask_step",
+EXPORTS = ("fdd_block_attn_workspace", "fdd_block_attn", "fdd_prefix_pack_bytes", "fdd_prefix_pack",
+           "fdd_unmask_workspace", "fdd_unmask_step",
            "fdd_fork_block", "fdd_block_kv_update", "fdd_profile_attn_events", "fdd_last_error", "fdd_version")
 
 
@@ -30,7 +31,8 @@ class AttnParams(C.Structure):
                 ("q", C.c_void_p), ("prefix_k", C.c_void_p), ("prefix_v", C.c_void_p),
                 ("block_k", C.c_void_p), ("block_v", C.c_void_p), ("scaffold_mask", C.c_void_p),
                 ("out", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("stream", C.c_void_p), ("splits", C.c_int32), ("reserved", C.c_int32)]
+                ("stream", C.c_void_p), ("splits", C.c_int32), ("reserved", C.c_int32),
+                ("prefix_v_packed", C.c_void_p)]
 
 
 class UnmaskParams(C.Structure):
@@ -66,6 +68,11 @@ def load_library():
         lib.fdd_block_attn_workspace.argtypes = [C.POINTER(AttnParams)]
         lib.fdd_block_attn.restype = C.c_int
         lib.fdd_block_attn.argtypes = [C.POINTER(AttnParams)]
+        lib.fdd_prefix_pack_bytes.restype = C.c_size_t
+        lib.fdd_prefix_pack_bytes.argtypes = [C.c_int32] * 4
+        lib.fdd_prefix_pack.restype = C.c_int
+        lib.fdd_prefix_pack.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_size_t,
+                                        C.c_void_p]
         lib.fdd_unmask_workspace.restype = C.c_size_t
         lib.fdd_unmask_workspace.argtypes = [C.POINTER(UnmaskParams)]
         lib.fdd_unmask_step.restype = C.c_int
@@ -138,7 +145,7 @@ def _workspace(ws, need, device):
     return ws, ws.numel() * ws.element_size()
 
 
-def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits):
+def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed=None):
     N, B, Hq, D = q.shape
     L, Hkv = prefix_k.shape[0], block_k.shape[2]
     if tuple(prefix_k.shape[1:]) != (Hkv, D) or tuple(prefix_v.shape) != tuple(prefix_k.shape):
@@ -159,22 +166,44 @@ def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, sc
     p.scaffold_mask = _dev(scaffold_mask, "scaffold_mask")
     p.out = _dev(out, "out") if out is not None else None
     p.splits = int(splits)
+    p.prefix_v_packed = _dev(prefix_v_packed, "prefix_v_packed")
     return p
 
 
-def fdd_block_attn_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0) -> int:
-    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, None, None, None, splits)
+def fdd_prefix_pack_bytes(prefix_v) -> int:
+    L, Hkv, D = prefix_v.shape
+    return load_library().fdd_prefix_pack_bytes(L, Hkv, D, _dtype_code(prefix_v))
+
+
+def fdd_prefix_pack(prefix_v, packed=None, stream=None):
+    """One-time relayout of the prefix V for later fdd_block_attn calls; returns
+    the packed buffer (None when there is nothing to pack)."""
+    import torch
+    lib = load_library()
+    L, Hkv, D = prefix_v.shape
+    need = lib.fdd_prefix_pack_bytes(L, Hkv, D, _dtype_code(prefix_v))
+    if need == 0:
+        return None
+    if packed is None:
+        packed = torch.empty(need, dtype=torch.uint8, device=prefix_v.device)
+    _check(lib.fdd_prefix_pack(_dev(prefix_v, "prefix_v"), L, Hkv, D, _dtype_code(prefix_v), _dev(packed, "packed"),
+                               packed.numel() * packed.element_size(), _stream_ptr(stream)))
+    return packed
+
+
+def fdd_block_attn_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0, prefix_v_packed=None) -> int:
+    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, None, None, None, splits, prefix_v_packed)
     return load_library().fdd_block_attn_workspace(C.byref(p))
 
 
 def fdd_block_attn(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask=None, out=None, scale=None,
-                   workspace=None, stream=None, splits=0):
+                   workspace=None, stream=None, splits=0, prefix_v_packed=None):
     """out[N,B,Hq,D] = shared-prefix block-causal attention (see include/fdd.h)."""
     import torch
     lib = load_library()
     if out is None:
         out = torch.empty_like(q)
-    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits)
+    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed)
     need = lib.fdd_block_attn_workspace(C.byref(p))
     ws, nbytes = _workspace(workspace, need, q.device)
     p.workspace = ws.data_ptr() if ws is not None else None

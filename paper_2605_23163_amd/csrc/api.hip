@@ -67,10 +67,18 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
         if (p.splits > 0) {
             w = NM * (p.splits < pl.TPU ? p.splits : pl.TPU);
         } else {
-            // one workgroup per compute unit, every one with the same number of
-            // key tiles; tiny problems keep two tiles per workgroup
-            w = pl.U < 2 * kNumCU ? (pl.U + 1) / 2 : kNumCU;
-            if (w > pl.U) w = pl.U;
+            // Equal pieces per M-tile when that fills at least 4/5 of the compute
+            // units: the workgroups of an XCD then walk the same K/V tiles in step
+            // and the prefix is fetched from HBM once.  Otherwise equal contiguous
+            // unit ranges (stream-K), two tiles or more per workgroup.
+            long long s = NM > 0 ? kNumCU / NM : 0;
+            if (s > pl.TPU / 2) s = pl.TPU / 2;
+            if (s >= 1 && NM * s * 5 >= (long long)kNumCU * 4) {
+                w = NM * s;
+            } else {
+                w = pl.U < 2 * kNumCU ? (pl.U + 1) / 2 : kNumCU;
+                if (w > pl.U) w = pl.U;
+            }
         }
         pl.W = (int)w;
         pl.splits = 0;
@@ -99,8 +107,10 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
         pl.ws_ml_bytes = 0;
     }
     // V is repacked once per call when more than one M-tile streams every V tile
+    // (or taken ready-made from the caller)
     pl.ws_vt_bytes = 0;
-    if (p.dtype == FDD_BF16 && pl.MT >= 2 && p.L >= pl.key_tile)
+    pl.packed = p.dtype == FDD_BF16 && p.L >= pl.key_tile && (pl.MT >= 2 || p.prefix_v_packed);
+    if (pl.packed && !p.prefix_v_packed)
         pl.ws_vt_bytes = (((size_t)p.Hkv * (p.L / pl.key_tile) * pl.key_tile * p.D * 2) + 255) & ~(size_t)255;
     *plan = pl;
     return true;
@@ -126,7 +136,7 @@ fdd_status fdd_block_attn(const fdd_attn_params* p)
     if (st != FDD_OK) return st;
     if (!p->q || !p->block_k || !p->block_v || !p->out) return fail(FDD_ERR_NULL, "fdd_block_attn: q, block_k, block_v and out must not be NULL");
     if (p->L > 0 && (!p->prefix_k || !p->prefix_v)) return fail(FDD_ERR_NULL, "fdd_block_attn: prefix_k / prefix_v is NULL with L=%d", p->L);
-    const void* ptrs[] = {p->q, p->prefix_k, p->prefix_v, p->block_k, p->block_v, p->out};
+    const void* ptrs[] = {p->q, p->prefix_k, p->prefix_v, p->block_k, p->block_v, p->out, p->prefix_v_packed};
     for (const void* x : ptrs)
         if (x && !aligned16(x)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: data pointers must be 16-byte aligned");
     if (p->out == p->q) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: out must not alias q");
@@ -154,6 +164,29 @@ fdd_status fdd_block_attn(const fdd_attn_params* p)
         e = launch_attn_combine(*p, plan, scale, s);
         if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: merge launch failed: %s", hipGetErrorString(e));
     }
+    return FDD_OK;
+}
+
+size_t fdd_prefix_pack_bytes(int32_t L, int32_t Hkv, int32_t D, int32_t dtype)
+{
+    if (dtype != FDD_BF16 || L < 64 || Hkv <= 0 || (D != 64 && D != 128)) return 0;
+    return (((size_t)Hkv * (L / 64) * 64 * D * 2) + 255) & ~(size_t)255;
+}
+
+fdd_status fdd_prefix_pack(const void* prefix_v, int32_t L, int32_t Hkv, int32_t D, int32_t dtype, void* packed,
+                           size_t packed_bytes, void* stream)
+{
+    if (dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_prefix_pack: only FDD_BF16 prefixes are packed");
+    if (L < 0 || Hkv <= 0) return fail(FDD_ERR_SHAPE, "fdd_prefix_pack: L must be >= 0 and Hkv positive");
+    if (D != 64 && D != 128) return fail(FDD_ERR_UNSUPPORTED, "fdd_prefix_pack: head size D=%d not supported (64 or 128)", D);
+    if ((long long)L * Hkv * D * 4 >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_prefix_pack: prefix V (L*Hkv*D elements) must stay below 2 GiB");
+    const size_t need = fdd_prefix_pack_bytes(L, Hkv, D, dtype);
+    if (need == 0) return FDD_OK;
+    if (!prefix_v || !packed) return fail(FDD_ERR_NULL, "fdd_prefix_pack: prefix_v and packed must not be NULL");
+    if (!aligned16(prefix_v) || !aligned16(packed)) return fail(FDD_ERR_UNSUPPORTED, "fdd_prefix_pack: pointers must be 16-byte aligned");
+    if (packed_bytes < need) return fail(FDD_ERR_WORKSPACE, "fdd_prefix_pack: packed buffer has %zu bytes, %zu needed", packed_bytes, need);
+    hipError_t e = launch_prefix_pack(prefix_v, L, Hkv, D, packed, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_prefix_pack: launch failed: %s", hipGetErrorString(e));
     return FDD_OK;
 }
 

@@ -176,8 +176,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     // Ranges are numbered so that the workgroups of one XCD own neighbouring
     // ranges: they stream the K/V of the same KV head a few tiles apart, and the
     // XCD's L2 serves all but the first of them.
-    const int wg = (a.W % kNumXCD == 0) ? (int)(blockIdx.x % kNumXCD) * (a.W / kNumXCD) + (int)(blockIdx.x / kNumXCD)
-                                        : (int)blockIdx.x;
+    const int per_xcd = (a.W + kNumXCD - 1) / kNumXCD;
+    const int wg = (int)(blockIdx.x % kNumXCD) * per_xcd + (int)(blockIdx.x / kNumXCD);
+    if (wg >= a.W) return;
     const long long u_end = a.U * (wg + 1) / a.W;
     for (long long u_cur = a.U * wg / a.W; u_cur < u_end;) {
     const int M = (int)(u_cur / a.TPU);              // M-tile index over all KV heads
@@ -696,7 +697,7 @@ __global__ __launch_bounds__(512) void vt_pack_kernel(const uint16_t* __restrict
 }
 
 template <int D, int WAVES, bool PACKED>
-hipError_t launch(const Args& a, hipStream_t stream, hipEvent_t before_main)
+hipError_t launch(const Args& a, bool pack_now, hipStream_t stream, hipEvent_t before_main)
 {
     using C = Cfg<D, WAVES>;
     const size_t lds_bytes = PACKED ? 4 * (size_t)C::T_BYTES : 2 * (size_t)C::BUF_BYTES;
@@ -709,7 +710,7 @@ hipError_t launch(const Args& a, hipStream_t stream, hipEvent_t before_main)
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    if (PACKED) {
+    if (PACKED && pack_now) {
         hipLaunchKernelGGL(vt_pack_kernel<D>, dim3(a.TPF, a.Hkv), dim3(512), 0, stream, a.pv, const_cast<uint16_t*>(a.vt),
                            a.Hkv, a.TPF);
         hipError_t e = hipGetLastError();
@@ -719,7 +720,8 @@ hipError_t launch(const Args& a, hipStream_t stream, hipEvent_t before_main)
         hipError_t e = hipEventRecord(before_main, stream);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kern, dim3(a.W), dim3(C::THREADS), lds_bytes, stream, a);
+    const int grid = (a.W + kNumXCD - 1) / kNumXCD * kNumXCD;   // padded so that every XCD gets the same count
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(C::THREADS), lds_bytes, stream, a);
     return hipGetLastError();
 }
 
@@ -739,15 +741,28 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     char* ws = static_cast<char*>(p.workspace);
     a.ws_o = reinterpret_cast<float*>(ws);
     a.ws_ml = reinterpret_cast<float*>(ws + plan.ws_o_bytes);
-    a.vt = reinterpret_cast<const uint16_t*>(ws + plan.ws_o_bytes + plan.ws_ml_bytes);
+    const bool pack_now = plan.packed && !p.prefix_v_packed;
+    a.vt = pack_now ? reinterpret_cast<const uint16_t*>(ws + plan.ws_o_bytes + plan.ws_ml_bytes)
+                    : static_cast<const uint16_t*>(p.prefix_v_packed);
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.TPF = p.L / 64;
     a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.U = plan.U;
     a.c = scale * 1.4426950408889634f;
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;
-    if (plan.ws_vt_bytes > 0)
-        return p.D == 128 ? launch<128, 8, true>(a, s, before_main) : launch<64, 8, true>(a, s, before_main);
-    return p.D == 128 ? launch<128, 8, false>(a, s, before_main) : launch<64, 8, false>(a, s, before_main);
+    if (plan.packed)
+        return p.D == 128 ? launch<128, 8, true>(a, pack_now, s, before_main) : launch<64, 8, true>(a, pack_now, s, before_main);
+    return p.D == 128 ? launch<128, 8, false>(a, false, s, before_main) : launch<64, 8, false>(a, false, s, before_main);
+}
+
+hipError_t launch_prefix_pack(const void* prefix_v, int L, int Hkv, int D, void* packed, hipStream_t s)
+{
+    const int TPF = L / KT;
+    if (TPF == 0) return hipSuccess;
+    const uint16_t* src = static_cast<const uint16_t*>(prefix_v);
+    uint16_t* dst = static_cast<uint16_t*>(packed);
+    if (D == 128) hipLaunchKernelGGL(vt_pack_kernel<128>, dim3(TPF, Hkv), dim3(512), 0, s, src, dst, Hkv, TPF);
+    else hipLaunchKernelGGL(vt_pack_kernel<64>, dim3(TPF, Hkv), dim3(512), 0, s, src, dst, Hkv, TPF);
+    return hipGetLastError();
 }
 
 }  // namespace fdd

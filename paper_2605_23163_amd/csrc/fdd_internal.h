@@ -41,12 +41,14 @@ struct AttnPlan {
     size_t ws_o_bytes;   // partial outputs  [Hkv*MT][max_seg][mtile_rows][D] fp32
     size_t ws_ml_bytes;  // partial (m, l)   [Hkv*MT][max_seg][mtile_rows][2] fp32
     size_t ws_vt_bytes;  // bf16 path: V of the full prefix tiles repacked for the P V fragments, or 0
+    bool packed;         // bf16 path: the kernel reads repacked V (from the workspace or from the caller)
 };
 
 bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan);
 
 // `before_main`, if not null, is recorded on the stream right before the main kernel (after the V pre-pass).
 hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s, hipEvent_t before_main);
+hipError_t launch_prefix_pack(const void* prefix_v, int L, int Hkv, int D, void* packed, hipStream_t s);
 hipError_t launch_attn_f32(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);
 hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);
 

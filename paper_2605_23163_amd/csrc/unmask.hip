@@ -29,6 +29,13 @@ namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int RTHREADS = 256;
+#ifndef FDD_UNROLL
+#define FDD_UNROLL 4
+#endif
+#ifndef FDD_PIECE_KB
+#define FDD_PIECE_KB 64
+#endif
+constexpr int UNROLL = FDD_UNROLL;   // 16-byte loads in flight per thread
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct Partial {
@@ -131,9 +138,7 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
             absorb<1>(r, x, (int)(v_lo + tid));
         }
         const u32x4* vp = reinterpret_cast<const u32x4*>(base + body0);
-        for (long long i = tid; i < nvec; i += RTHREADS) {
-            const u32x4 raw = __builtin_nontemporal_load(vp + i);
-            float x[VEC];
+        auto widen = [&](const u32x4& raw, float (&x)[VEC]) {
             if (sizeof(T) == 2) {
                 const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
@@ -147,6 +152,24 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
                 x[2] = __uint_as_float(raw.z);
                 x[3] = __uint_as_float(raw.w);
             }
+        };
+        // UNROLL independent 16-byte loads in flight per thread, absorbed in ascending order
+        long long i = tid;
+        for (; i + (UNROLL - 1) * RTHREADS < nvec; i += UNROLL * RTHREADS) {
+            u32x4 raw[UNROLL];
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) raw[u] = __builtin_nontemporal_load(vp + i + u * RTHREADS);
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                float x[VEC];
+                widen(raw[u], x);
+                absorb<VEC>(r, x, (int)(body0 + (i + u * RTHREADS) * VEC));
+            }
+        }
+        for (; i < nvec; i += RTHREADS) {
+            const u32x4 raw = __builtin_nontemporal_load(vp + i);
+            float x[VEC];
+            widen(raw, x);
             absorb<VEC>(r, x, (int)(body0 + i * VEC));
         }
         const long long ntail = v_hi - tail0;
@@ -182,7 +205,7 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
     }
 }
 
-constexpr int STHREADS = 256;
+constexpr int STHREADS = 64;   // one wavefront per rollout: no LDS, no workgroup barrier
 
 __global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
 {
@@ -190,7 +213,7 @@ __global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
     const int tid = threadIdx.x;
     const double tau = (double)a.tau;
 
-    int my_count = 0;
+    int count = 0;
     double best_conf = -1.0;     // confidences are positive
     int best_b = 0x7fffffff;
     int best_tok = -1;
@@ -207,51 +230,38 @@ __global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
             int arg = p[0].arg;
             for (int s = 1; s < a.vsplits; ++s)
                 if (p[s].m > M) { M = p[s].m; arg = p[s].arg; }
+            // sum of the pieces' fp32 sums, rescaled to the row maximum, finished in fp64
             double z = 0.0;
             for (int s = 0; s < a.vsplits; ++s)
-                if (p[s].s > 0.f) z += (double)p[s].s * exp2((double)(p[s].m - M) * 1.4426950408889634);
+                if (p[s].s > 0.f) z += (double)(p[s].s * fast_exp2((p[s].m - M) * LOG2E));
             const double conf = 1.0 / z;
             conf_out = (float)conf;
             if (conf >= tau) {
                 a.tokens[i] = arg;
                 a.mask[i] = 0;
                 com = 1;
-                ++my_count;
+                ++count;
             }
             if (conf > best_conf) { best_conf = conf; best_b = b; best_tok = arg; }   // ascending b per thread
         }
         a.conf[i] = conf_out;
         if (a.committed) a.committed[i] = com;
     }
-
-    __shared__ int s_count[STHREADS];
-    __shared__ double s_conf[STHREADS];
-    __shared__ int s_b[STHREADS];
-    __shared__ int s_tok[STHREADS];
-    s_count[tid] = my_count;
-    s_conf[tid] = best_conf;
-    s_b[tid] = best_b;
-    s_tok[tid] = best_tok;
-    __syncthreads();
-    for (int off = STHREADS / 2; off >= 1; off >>= 1) {
-        if (tid < off) {
-            s_count[tid] += s_count[tid + off];
-            const bool take = (s_conf[tid + off] > s_conf[tid]) ||
-                              (s_conf[tid + off] == s_conf[tid] && s_b[tid + off] < s_b[tid]);
-            if (take) {
-                s_conf[tid] = s_conf[tid + off];
-                s_b[tid] = s_b[tid + off];
-                s_tok[tid] = s_tok[tid + off];
-            }
-        }
-        __syncthreads();
+    // wavefront reduction: commits are summed; the best candidate is the one of
+    // highest confidence, lowest position on ties
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        count += __shfl_xor(count, off, 64);
+        const double oc = __shfl_xor(best_conf, off, 64);
+        const int ob = __shfl_xor(best_b, off, 64);
+        const int ot = __shfl_xor(best_tok, off, 64);
+        if (oc > best_conf || (oc == best_conf && ob < best_b)) { best_conf = oc; best_b = ob; best_tok = ot; }
     }
     if (tid == 0) {
-        int count = s_count[0];
-        if (count == 0 && s_tok[0] >= 0) {
+        if (count == 0 && best_tok >= 0) {
             // nothing reached tau: commit the most confident eligible position
-            const size_t i = (size_t)n * a.B + s_b[0];
-            a.tokens[i] = s_tok[0];
+            const size_t i = (size_t)n * a.B + best_b;
+            a.tokens[i] = best_tok;
             a.mask[i] = 0;
             if (a.committed) a.committed[i] = 1;
             count = 1;
@@ -267,7 +277,7 @@ bool make_unmask_plan(const fdd_unmask_params& p, UnmaskPlan* plan)
     if (p.N <= 0 || p.B <= 0 || p.V <= 0) return false;
     const long long rows = (long long)p.N * p.B;
     const long long es = p.dtype == FDD_BF16 ? 2 : 4;
-    long long by_size = (p.V * es) / 16384;     // keep pieces at 16 KiB or more
+    long long by_size = (p.V * es) / (FDD_PIECE_KB * 1024);     // keep pieces at this size or more
     if (by_size < 1) by_size = 1;
     long long want = (8192 + rows - 1) / rows;  // enough workgroups to fill 256 CUs several times
     if (want < 1) want = 1;

@@ -93,6 +93,20 @@ def test_unmask_workspace_and_errors(lib):
     assert lib.fdd_unmask_step(None) == 1
 
 
+def test_prefix_pack_sizes_and_errors(lib):
+    assert lib.fdd_prefix_pack_bytes(16384, 4, 128, bd.FDD_BF16) == 16384 * 4 * 128 * 2
+    assert lib.fdd_prefix_pack_bytes(100, 2, 64, bd.FDD_BF16) == 64 * 2 * 64 * 2     # full tiles only
+    assert lib.fdd_prefix_pack_bytes(63, 4, 128, bd.FDD_BF16) == 0
+    assert lib.fdd_prefix_pack_bytes(4096, 4, 128, bd.FDD_F32) == 0
+    assert lib.fdd_prefix_pack(256, 4096, 4, 128, bd.FDD_F32, 512, 1 << 30, None) == 3
+    assert lib.fdd_prefix_pack(256, 4096, 4, 96, bd.FDD_BF16, 512, 1 << 30, None) == 4
+    assert lib.fdd_prefix_pack(None, 4096, 4, 128, bd.FDD_BF16, 512, 1 << 30, None) == 1
+    assert lib.fdd_prefix_pack(256, 4096, 4, 128, bd.FDD_BF16, 512, 1024, None) == 5
+    assert lib.fdd_prefix_pack(256, 4096, 0, 128, bd.FDD_BF16, 512, 1 << 30, None) == 2
+    assert lib.fdd_prefix_pack(256, 10, 4, 128, bd.FDD_BF16, None, 0, None) == 0       # nothing to pack
+    assert lib.fdd_last_error().decode().startswith("fdd_prefix_pack:")
+
+
 def test_bookkeeping_errors(lib):
     assert lib.fdd_fork_block(4, 64, None, 4096, None) == 1
     assert lib.fdd_fork_block(0, 64, 256, 4096, None) == 2

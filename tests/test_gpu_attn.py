@@ -154,6 +154,31 @@ def test_other_rollouts_blocks_are_invisible_and_scaffold_mask_is_inert(F):
     assert torch.equal(a, c)
 
 
+def test_prepacked_prefix_v_gives_the_same_bits(F, oracle):
+    print_case(test="attn_prefix_pack")
+    rng = np.random.default_rng(15)
+    for shape in [(4, 32, 1000, 28, 4, 128), (1, 16, 300, 4, 2, 64), (3, 40, 64, 8, 2, 128), (2, 8, 63, 4, 1, 64)]:
+        N, B, L, Hq, Hkv, D = shape
+        d = rand_attn(rng, N, B, L, Hq, Hkv, D, W.BF16)
+        t = {k: to_dev(v) for k, v in d.items()}
+        packed = F.fdd_prefix_pack(t["prefix_v"])
+        assert (packed is None) == (L < 64)
+        plain = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"])
+        pre = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"], prefix_v_packed=packed)
+        torch.cuda.synchronize()
+        ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"])
+        assert np.abs(to_f64(pre) - ref).max() <= 2e-2
+        if N * B * (Hq // Hkv) > 256:
+            # the call packs V itself when several M-tiles share it: same kernel, same bits
+            assert torch.equal(plain, pre)
+        # the workspace shrinks by the packed copy when the caller brings it
+        if packed is not None and N * B * (Hq // Hkv) > 256:
+            a = F.fdd_block_attn_workspace(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"])
+            b = F.fdd_block_attn_workspace(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"],
+                                           prefix_v_packed=packed)
+            assert a - b == F.fdd_prefix_pack_bytes(t["prefix_v"])
+
+
 def test_repeated_calls_are_bitwise_reproducible(F):
     print_case(test="attn_repro")
     d = W.attention_inputs(W.CONFIGS["cfg2"])
