@@ -37,6 +37,10 @@ if ROOT not in sys.path:
 PEAK_HBM_GBS = 8000.0
 PEAK_BF16_TFLOPS = 2500.0
 STEPS_PER_BLOCK = 8
+# HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each scaled
+# by what the same counter reads for a 1 GiB device copy (0.5x and 1.0x); summary and commands in
+# profiles/bench_cfg5_denoise_step.md.  (read MiB, write MiB) per launch.
+MEASURED_TRAFFIC_MIB = {"cfg5": {"attn_bf16_kernel": (50.1, 31.1), "vocab_reduce_kernel": (193.0, 0.1)}}
 
 
 def dev(a):
@@ -243,7 +247,10 @@ def main():
         "wall_ms_per_step": round(wall * 1e3 / args.steps, 4),
         "roofline": {"kernel": "attn_bf16_kernel", "bound": "mfma", "achieved": round(flops / (attn_ms * 1e-3) / 1e12, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "traffic": (round(sum(MEASURED_TRAFFIC_MIB[w.name]["attn_bf16_kernel"]) * 2 ** 20)
+                                 if w.name in MEASURED_TRAFFIC_MIB else None),
+                     "algorithmic_bytes": attn_bytes(w)[1],
                      "flops_per_launch": flops, "avg_launch_us": round(attn_ms * 1e3, 2)},
     }
     if has_unmask:
@@ -259,7 +266,9 @@ def main():
         # forced single commit per block per step at these logit statistics: rows = elig0 - N * (step in block)
         avg_rows = elig0 - w.N * (STEPS_PER_BLOCK - 1) / 2.0
         byt = avg_rows * w.V * 2
-        res["roofline_unmask"].update({"achieved": round(byt / (un_ms * 1e-3) / 1e9, 1),
+        res["roofline_unmask"].update({"traffic": (round(sum(MEASURED_TRAFFIC_MIB[w.name]["vocab_reduce_kernel"]) * 2 ** 20)
+                                                   if w.name in MEASURED_TRAFFIC_MIB else None),
+                                       "achieved": round(byt / (un_ms * 1e-3) / 1e9, 1),
                                        "frac": round(byt / (un_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                        "bytes_per_call": byt})
     if not args.no_supplements:

@@ -64,8 +64,10 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
     bool partials;
     if (p.dtype == FDD_BF16) {
         long long w;
+        pl.uniform = 0;
         if (p.splits > 0) {
-            w = NM * (p.splits < pl.TPU ? p.splits : pl.TPU);
+            pl.uniform = p.splits < pl.TPU ? p.splits : pl.TPU;
+            w = NM * pl.uniform;
         } else {
             // Equal pieces per M-tile when that fills at least 4/5 of the compute
             // units: the workgroups of an XCD then walk the same K/V tiles in step
@@ -75,6 +77,7 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
             if (s > pl.TPU / 2) s = pl.TPU / 2;
             if (s >= 1 && NM * s * 5 >= (long long)kNumCU * 4) {
                 w = NM * s;
+                pl.uniform = (int)s;
             } else {
                 w = pl.U < 2 * kNumCU ? (pl.U + 1) / 2 : kNumCU;
                 if (w > pl.U) w = pl.U;
@@ -95,6 +98,7 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
         if (s < 1) s = 1;
         pl.splits = s;
         pl.W = 0;
+        pl.uniform = 0;
         pl.max_seg = s;
         partials = s > 1;
     }

@@ -92,6 +92,7 @@ struct Args {
     int TPU;        // units per M-tile = max(TP, 1)
     int W;          // workgroups
     int max_seg;    // partial slots per M-tile
+    int S;          // > 0: every M-tile is cut into S equal pieces (W = Hkv*MT*S); 0: free ranges
     long long U;    // units in total = Hkv * MT * TPU
     float c;        // scale * log2(e)
 };
@@ -174,11 +175,16 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     // ---- stream-K: this workgroup's contiguous range of (M-tile, prefix tile) units
     // Workgroups are dealt to the 8 XCDs round-robin by their launch index.
     // Ranges are numbered so that the workgroups of one XCD own neighbouring
-    // ranges: they stream the K/V of the same KV head a few tiles apart, and the
-    // XCD's L2 serves all but the first of them.
+    // ranges.
     const int per_xcd = (a.W + kNumXCD - 1) / kNumXCD;
-    const int wg = (int)(blockIdx.x % kNumXCD) * per_xcd + (int)(blockIdx.x / kNumXCD);
+    int wg = (int)(blockIdx.x % kNumXCD) * per_xcd + (int)(blockIdx.x / kNumXCD);
     if (wg >= a.W) return;
+    if (a.S > 0) {
+        // equal pieces: neighbours are the M-tiles of one (KV head, piece), which
+        // walk the same keys in step, so each XCD fetches its share of K/V once
+        const int mt_ = wg % a.MT, piece = (wg / a.MT) % a.S, kh_ = wg / (a.MT * a.S);
+        wg = (kh_ * a.MT + mt_) * a.S + piece;
+    }
     const long long u_end = a.U * (wg + 1) / a.W;
     for (long long u_cur = a.U * wg / a.W; u_cur < u_end;) {
     const int M = (int)(u_cur / a.TPU);              // M-tile index over all KV heads
@@ -746,7 +752,7 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
                     : static_cast<const uint16_t*>(p.prefix_v_packed);
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.TPF = p.L / 64;
-    a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.U = plan.U;
+    a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.U = plan.U; a.S = plan.uniform;
     a.c = scale * 1.4426950408889634f;
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;
     if (plan.packed)

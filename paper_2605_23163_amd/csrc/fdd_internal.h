@@ -36,6 +36,7 @@ struct AttnPlan {
     int splits;       // fp32 path: pieces along L
     int TPU;          // bf16 path: units per M-tile = max(TP, 1)
     int W;            // bf16 path: workgroups
+    int uniform;      // bf16 path: > 0 when W = Hkv*MT*uniform, i.e. equal pieces per M-tile
     long long U;      // bf16 path: units in total
     int max_seg;      // partial slots per M-tile
     size_t ws_o_bytes;   // partial outputs  [Hkv*MT][max_seg][mtile_rows][D] fp32
