@@ -81,6 +81,10 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
             } else {
                 w = pl.U < 2 * kNumCU ? (pl.U + 1) / 2 : kNumCU;
                 if (w > pl.U) w = pl.U;
+                if (w <= NM && NM <= kNumCU) {   // nothing to gain from cutting M-tiles: one workgroup each
+                    w = NM;
+                    pl.uniform = 1;
+                }
             }
         }
         pl.W = (int)w;

@@ -213,8 +213,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     const int wg_n_hi = (min(row0_wg + MROWS - 1, a.R - 1)) / BG;
 
     // ---- Q fragments: B operand of S^T = K Q^T ------------------------------
+    // (loaded after the first K/V tiles have been requested, so the two latencies overlap)
     bf16x8 qf[KS];
-    {
+    auto load_q = [&]() {
         const uint16_t* qp = a.q + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D + half * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             if (row_ok) raw = *reinterpret_cast<const u32x4*>(qp + ks * 16);
             qf[ks] = __builtin_bit_cast(bf16x8, raw);
         }
-    }
+    };
 
     // ---- tile schedule -------------------------------------------------------
     const int t0 = min(t_begin, a.TP);
@@ -442,6 +443,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         // prologue: K(0), V(0) and K(1) into LDS, scores of tile 0
         fetch_k(0, 0);
         fetch_v(0, 0);
+        load_q();
         if (!PACKED) {
             store_k(0);
             store_v(0);
@@ -588,6 +590,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         } else {
             step(even, last, i, sa, sb);
         }
+    } else {
+        load_q();
     }
     f32x16 s[2];      // scores of a masked tile
 
