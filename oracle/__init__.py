@@ -39,6 +39,10 @@ def _load():
         c = ctypes
         lib.fddo_block_attn.restype = c.c_int
         lib.fddo_block_attn.argtypes = [c.c_int] * 7 + [c.c_double] + [c.c_void_p] * 6 + [c.c_int64, c.c_void_p]
+        lib.fddo_block_attn_ex.restype = c.c_int
+        lib.fddo_block_attn_ex.argtypes = [c.c_int] * 7 + [c.c_double, c.c_int] + [c.c_void_p] * 6 + [c.c_int64, c.c_void_p]
+        lib.fddo_verify_step.restype = c.c_int
+        lib.fddo_verify_step.argtypes = [c.c_int, c.c_int, c.c_int64, c.c_int] + [c.c_void_p] * 8
         lib.fddo_unmask_step.restype = c.c_int
         lib.fddo_unmask_step.argtypes = [c.c_int, c.c_int, c.c_int64, c.c_int, c.c_double] + [c.c_void_p] * 8
         lib.fddo_block_kv_update.restype = c.c_int
@@ -68,8 +72,9 @@ def _same_storage(*arrs):
     return arrs, _DT[dt]
 
 
-def block_attn(q, prefix_k, prefix_v, block_k, block_v, scale=None, rows=None):
-    """Block-causal shared-prefix attention in fp64.
+def block_attn(q, prefix_k, prefix_v, block_k, block_v, scale=None, rows=None, causal_block=False):
+    """Block-causal shared-prefix attention in fp64.  ``causal_block=True`` makes
+    the in-block part causal (the verify pass of scaffold speculative decoding).
 
     q [N,B,Hq,D], prefix_k/v [L,Hkv,D], block_k/v [N,B,Hkv,D]; float64,
     float32, or uint16 holding bf16 bits.  ``rows``: optional int array
@@ -88,8 +93,8 @@ def block_attn(q, prefix_k, prefix_v, block_k, block_v, scale=None, rows=None):
         r = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 3)
         nr = r.shape[0]
         out = np.empty((nr, D), dtype=np.float64)
-    rc = _load().fddo_block_attn(N, B, L, Hq, Hkv, D, dt, scale, _ptr(q), _ptr(prefix_k), _ptr(prefix_v),
-                                 _ptr(block_k), _ptr(block_v), _ptr(r), nr, _ptr(out))
+    rc = _load().fddo_block_attn_ex(N, B, L, Hq, Hkv, D, dt, scale, int(bool(causal_block)), _ptr(q), _ptr(prefix_k),
+                                    _ptr(prefix_v), _ptr(block_k), _ptr(block_v), _ptr(r), nr, _ptr(out))
     if rc:
         raise ValueError("fddo_block_attn rejected its arguments")
     return out
@@ -116,6 +121,28 @@ def unmask_step(logits, mask, scaffold_mask, tokens, tau):
     if rc:
         raise ValueError("fddo_unmask_step rejected its arguments")
     return dict(tokens=tokens, mask=mask, confidences=conf, candidates=cand, n_unmasked=nun, committed=com)
+
+
+def verify_step(ar_logits, mask, scaffold_mask, draft, tokens):
+    """Accept scan of scaffold speculative decoding; inputs are not modified.
+
+    Returns dict(tokens, mask, ar_tokens, n_accepted, accepted).
+    """
+    ar_logits = np.ascontiguousarray(ar_logits)
+    dt = _DT[ar_logits.dtype]
+    N, B, V = ar_logits.shape
+    mask = np.array(mask, dtype=np.uint8, order="C", copy=True).reshape(N, B)
+    tokens = np.array(tokens, dtype=np.int32, order="C", copy=True).reshape(N, B)
+    draft = np.ascontiguousarray(draft, dtype=np.int32).reshape(N, B)
+    sc = None if scaffold_mask is None else np.ascontiguousarray(scaffold_mask, dtype=np.uint8).reshape(N, B)
+    ar = np.empty((N, B), dtype=np.int32)
+    nacc = np.empty((N,), dtype=np.int32)
+    acc = np.empty((N, B), dtype=np.uint8)
+    rc = _load().fddo_verify_step(N, B, V, dt, _ptr(ar_logits), _ptr(sc), _ptr(draft), _ptr(mask), _ptr(tokens),
+                                  _ptr(ar), _ptr(nacc), _ptr(acc))
+    if rc:
+        raise ValueError("fddo_verify_step rejected its arguments")
+    return dict(tokens=tokens, mask=mask, ar_tokens=ar, n_accepted=nacc, accepted=acc)
 
 
 def block_kv_update(tokens, committed, table_k, table_v, block_k, block_v):

@@ -20,6 +20,20 @@
  *                       weighted sum of the value rows.  No tiling, no
  *                       streaming softmax, no reordering.
  *
+ *                       With causal_block != 0 the in-block part is causal
+ *                       instead: block position b sees block positions <= b.
+ *                       That is the verify pass of Scaffold Speculative
+ *                       Decoding (paper, "Scaffold Speculative Decoding (SS)",
+ *                       step 3: "a causal forward pass over the entire block").
+ *
+ *  fddo_verify_step     The accept rule of the same step 3: value positions
+ *                       are visited left to right; a draft token equal to the
+ *                       arg max of the AR distribution at its position is
+ *                       accepted; at the first mismatch the AR token replaces
+ *                       the draft (the one bonus token) and every later draft
+ *                       is discarded.  Scaffold positions are auto-accepted
+ *                       (step 1) and do not take part.
+ *
  *  fddo_unmask_step     One iteration of "iteratively unmasks value
  *                       positions" (paper, "Section Diffusion (SD)") under the
  *                       masked-diffusion rule that visible tokens stay fixed
@@ -85,19 +99,34 @@ static size_t elem_size(int dtype) { return dtype == 0 ? 8 : dtype == 1 ? 4 : 2;
  * the KV head h / (Hq/Hkv).  rows == NULL: all (n,b,h), out is [N,B,Hq,D].
  * rows != NULL: n_rows triples (n,b,h); out is [n_rows,D].
  */
+int fddo_block_attn_ex(int N, int B, int L, int Hq, int Hkv, int D, int dtype, double scale, int causal_block,
+                       const void *q, const void *prefix_k, const void *prefix_v,
+                       const void *block_k, const void *block_v,
+                       const int32_t *rows, int64_t n_rows, double *out);
+
 int fddo_block_attn(int N, int B, int L, int Hq, int Hkv, int D, int dtype, double scale,
                     const void *q, const void *prefix_k, const void *prefix_v,
                     const void *block_k, const void *block_v,
                     const int32_t *rows, int64_t n_rows, double *out)
 {
+    return fddo_block_attn_ex(N, B, L, Hq, Hkv, D, dtype, scale, 0, q, prefix_k, prefix_v, block_k, block_v,
+                              rows, n_rows, out);
+}
+
+/* causal_block == 0: the whole own block is visible; != 0: block keys up to the query's own position. */
+int fddo_block_attn_ex(int N, int B, int L, int Hq, int Hkv, int D, int dtype, double scale, int causal_block,
+                       const void *q, const void *prefix_k, const void *prefix_v,
+                       const void *block_k, const void *block_v,
+                       const int32_t *rows, int64_t n_rows, double *out)
+{
     if (N <= 0 || B <= 0 || L < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv) return 1;
     const int G = Hq / Hkv;
-    const int S = L + B;
+    const int Sfull = L + B;
     const int64_t total = rows ? n_rows : (int64_t)N * B * Hq;
     int bad = 0;
 #pragma omp parallel
     {
-        double *s = (double *)malloc(sizeof(double) * (size_t)S);
+        double *s = (double *)malloc(sizeof(double) * (size_t)Sfull);
 #pragma omp for schedule(dynamic, 4)
         for (int64_t r = 0; r < total; ++r) {
             int n, b, h;
@@ -105,6 +134,7 @@ int fddo_block_attn(int N, int B, int L, int Hq, int Hkv, int D, int dtype, doub
             else { h = (int)(r % Hq); b = (int)((r / Hq) % B); n = (int)(r / ((int64_t)Hq * B)); }
             if (n < 0 || n >= N || b < 0 || b >= B || h < 0 || h >= Hq) { bad = 1; continue; }
             const int kh = h / G;
+            const int S = causal_block ? L + b + 1 : Sfull;   /* number of visible keys */
             const size_t qo = (((size_t)n * B + b) * Hq + h) * D;
             /* scores over every visible key: the prefix, then the own block */
             double smax = -INFINITY;
@@ -196,6 +226,52 @@ int fddo_unmask_step(int N, int B, int64_t V, int dtype, double tau, const void 
     }
     if (cand) memcpy(cand, tok, sizeof(int32_t) * (size_t)NB);
     free(tok);
+    return 0;
+}
+
+/*
+ * Verify pass of scaffold speculative decoding over N blocks.  A position is a
+ * draft position when mask == 1 and it is not scaffold.  mask and tokens are
+ * updated in place: accepted positions take their draft token, the rejection
+ * point takes the AR token, both are unmasked; later draft positions stay masked
+ * and keep their tokens entry.
+ *   ar_tok[n,b]     arg max of the AR logits at draft positions (lowest id on
+ *                   ties), -1 elsewhere (may be NULL)
+ *   n_accepted[n]   positions unmasked in block n by this call
+ *   accepted[n,b]   1 = draft accepted, 2 = replaced by the AR token, 0 otherwise (may be NULL)
+ */
+int fddo_verify_step(int N, int B, int64_t V, int dtype, const void *ar_logits, const uint8_t *scaffold,
+                     const int32_t *draft, uint8_t *mask, int32_t *tokens, int32_t *ar_tok,
+                     int32_t *n_accepted, uint8_t *accepted)
+{
+    if (N <= 0 || B <= 0 || V <= 0) return 1;
+    for (int n = 0; n < N; ++n) {
+        int count = 0, rejected = 0;
+        for (int b = 0; b < B; ++b) {
+            const int64_t i = (int64_t)n * B + b;
+            const int is_draft = mask[i] == 1 && !(scaffold && scaffold[i]);
+            if (accepted) accepted[i] = 0;
+            if (ar_tok) ar_tok[i] = -1;
+            if (!is_draft) continue;
+            const size_t base = (size_t)i * (size_t)V;
+            double xmax = widen(ar_logits, dtype, base);
+            int64_t arg = 0;
+            for (int64_t v = 1; v < V; ++v) {
+                const double x = widen(ar_logits, dtype, base + v);
+                if (x > xmax) { xmax = x; arg = v; }
+            }
+            if (ar_tok) ar_tok[i] = (int32_t)arg;
+            if (rejected) continue;                 /* discarded: stays masked */
+            if ((int32_t)arg == draft[i]) {
+                tokens[i] = draft[i]; mask[i] = 0; ++count;
+                if (accepted) accepted[i] = 1;
+            } else {
+                tokens[i] = (int32_t)arg; mask[i] = 0; ++count; rejected = 1;
+                if (accepted) accepted[i] = 2;
+            }
+        }
+        if (n_accepted) n_accepted[n] = count;
+    }
     return 0;
 }
 

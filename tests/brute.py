@@ -9,7 +9,7 @@ import math
 import numpy as np
 
 
-def visibility_matrix(N, B, L):
+def visibility_matrix(N, B, L, causal_block=False):
     """vis[i, j] = may token i attend to token j.
 
     Token order: L prefix tokens, then rollout 0's block, rollout 1's, ...
@@ -24,16 +24,16 @@ def visibility_matrix(N, B, L):
     for n in range(N):
         lo, hi = L + n * B, L + (n + 1) * B
         vis[lo:hi, :L] = True
-        vis[lo:hi, lo:hi] = True
+        vis[lo:hi, lo:hi] = np.tril(np.ones((B, B), dtype=bool)) if causal_block else True
     return vis
 
 
-def attention_explicit_mask(q, pk, pv, bk, bv, scale):
+def attention_explicit_mask(q, pk, pv, bk, bv, scale, causal_block=False):
     """Dense masked attention over the concatenated sequence, float64."""
     N, B, Hq, D = q.shape
     L, Hkv, _ = pk.shape
     G = Hq // Hkv
-    vis = visibility_matrix(N, B, L)[L:, :]                     # block rows only
+    vis = visibility_matrix(N, B, L, causal_block)[L:, :]       # block rows only
     out = np.zeros((N, B, Hq, D))
     for h in range(Hq):
         kh = h // G
@@ -76,3 +76,28 @@ def unmask_python(logits, mask, scaffold, tokens, tau):
             mask[n][b] = 0
         nun[n] = len(chosen)
     return np.array(tokens, dtype=np.int32), np.array(mask, dtype=np.uint8), np.array(conf), np.array(nun, dtype=np.int32)
+
+
+def verify_python(ar_logits, mask, scaffold, draft, tokens):
+    """Accept scan of scaffold speculative decoding in plain Python."""
+    N, B, V = ar_logits.shape
+    tokens = [list(map(int, r)) for r in tokens]
+    mask = [list(map(int, r)) for r in mask]
+    nacc = [0] * N
+    for n in range(N):
+        alive = True
+        for b in range(B):
+            if mask[n][b] != 1 or scaffold[n][b]:
+                continue                     # scaffold / already visible: auto-accepted, not verified
+            if not alive:
+                continue                     # discarded draft stays masked
+            row = [float(x) for x in ar_logits[n, b]]
+            ar = row.index(max(row))
+            if ar == int(draft[n][b]):
+                tokens[n][b] = int(draft[n][b])
+            else:
+                tokens[n][b] = ar
+                alive = False
+            mask[n][b] = 0
+            nacc[n] += 1
+    return np.array(tokens, dtype=np.int32), np.array(mask, dtype=np.uint8), np.array(nacc, dtype=np.int32)
