@@ -76,6 +76,13 @@ typedef enum { FDD_F32 = 0, FDD_BF16 = 1 } fdd_dtype;
  * (0 = chosen by the library); the result does not depend on it beyond
  * fp32 rounding.
  */
+/* In-block attention is causal instead of bidirectional: block position b sees
+ * the prefix and block positions <= b of its own rollout.  This is the verify
+ * pass of Scaffold Speculative Decoding (paper, "Scaffold Speculative Decoding
+ * (SS)", step 3: "a causal forward pass over the entire block"); the draft pass
+ * of step 2 is the default bidirectional form. */
+#define FDD_ATTN_CAUSAL_BLOCK 1
+
 typedef struct fdd_attn_params {
     int32_t N, B, L, Hq, Hkv, D;
     int32_t dtype;                 /* fdd_dtype of q, k, v and out */
@@ -91,7 +98,7 @@ typedef struct fdd_attn_params {
     size_t workspace_bytes;
     void *stream;                  /* hipStream_t */
     int32_t splits;                /* 0 = automatic */
-    int32_t reserved;              /* must be 0 */
+    int32_t flags;                 /* FDD_ATTN_* bits; unknown bits are rejected */
     const void *prefix_v_packed;   /* optional: output of fdd_prefix_pack for this prefix_v, or NULL */
 } fdd_attn_params;
 
@@ -161,6 +168,43 @@ typedef struct fdd_unmask_params {
 
 size_t fdd_unmask_workspace(const fdd_unmask_params *p);
 fdd_status fdd_unmask_step(const fdd_unmask_params *p);
+
+/* ------------------------------------------------------------------------
+ * fdd_verify_step: accept scan of Scaffold Speculative Decoding over N blocks
+ * (paper, "Scaffold Speculative Decoding (SS)", steps 1 and 3).
+ *
+ * Draft positions are those with mask[n,b] == 1 and scaffold_mask[n,b] == 0;
+ * scaffold positions are auto-accepted and take no part.  ar_logits[n,b,:] is
+ * the AR head's distribution for the token AT position b (the caller applies
+ * the usual one-position shift).  Draft positions are visited left to right:
+ * while the lowest id attaining max_v ar_logits[n,b,v] equals draft[n,b], the
+ * draft is accepted (tokens[n,b] = draft[n,b], mask cleared).  At the first
+ * mismatch the AR token replaces the draft (tokens[n,b] = arg max, mask
+ * cleared: the one bonus token) and every later draft position of the block
+ * is discarded: its mask bit stays 1 and its tokens entry is not touched.
+ * n_accepted[n] counts the positions unmasked by this call; accepted[n,b] is
+ * 1 for an accepted draft, 2 for the replaced position, 0 otherwise.
+ * Only the logits rows of draft positions are read.
+ */
+typedef struct fdd_verify_params {
+    int32_t N, B;
+    int64_t V;
+    int32_t dtype;                 /* fdd_dtype of ar_logits */
+    int32_t reserved;              /* must be 0 */
+    const void *ar_logits;         /* [N,B,V] */
+    const uint8_t *scaffold_mask;  /* [N,B]; may be NULL */
+    const int32_t *draft;          /* [N,B] draft tokens (read at draft positions only) */
+    uint8_t *mask;                 /* [N,B] in/out */
+    int32_t *tokens;               /* [N,B] in/out */
+    int32_t *n_accepted;           /* [N] out; may be NULL */
+    uint8_t *accepted;             /* [N,B] out; may be NULL */
+    void *workspace;               /* >= fdd_verify_workspace() bytes */
+    size_t workspace_bytes;
+    void *stream;
+} fdd_verify_params;
+
+size_t fdd_verify_workspace(const fdd_verify_params *p);
+fdd_status fdd_verify_step(const fdd_verify_params *p);
 
 /* ------------------------------------------------------------------------
  * Rollout-fork bookkeeping ("fork the KV cache N times").

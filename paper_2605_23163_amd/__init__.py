@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     fdd_profile_attn_events,
     fdd_unmask_step,
     fdd_unmask_workspace,
+    fdd_verify_step,
     fdd_version,
     library_path,
     load_library,

@@ -14,8 +14,9 @@ _LIB_PATH = os.path.join(_HERE, "libfdd.so")
 _lib = None
 
 FDD_F32, FDD_BF16 = 0, 1
+FDD_ATTN_CAUSAL_BLOCK = 1
 EXPORTS = ("fdd_block_attn_workspace", "fdd_block_attn", "fdd_prefix_pack_bytes", "fdd_prefix_pack",
-           "fdd_unmask_workspace", "fdd_unmask_step",
+           "fdd_unmask_workspace", "fdd_unmask_step", "fdd_verify_workspace", "fdd_verify_step",
            "fdd_fork_block", "fdd_block_kv_update", "fdd_profile_attn_events", "fdd_last_error", "fdd_version")
 
 
@@ -31,7 +32,7 @@ class AttnParams(C.Structure):
                 ("q", C.c_void_p), ("prefix_k", C.c_void_p), ("prefix_v", C.c_void_p),
                 ("block_k", C.c_void_p), ("block_v", C.c_void_p), ("scaffold_mask", C.c_void_p),
                 ("out", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("stream", C.c_void_p), ("splits", C.c_int32), ("reserved", C.c_int32),
+                ("stream", C.c_void_p), ("splits", C.c_int32), ("flags", C.c_int32),
                 ("prefix_v_packed", C.c_void_p)]
 
 
@@ -41,6 +42,13 @@ class UnmaskParams(C.Structure):
                 ("tokens", C.c_void_p), ("confidences", C.c_void_p), ("n_unmasked", C.c_void_p),
                 ("committed", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
                 ("stream", C.c_void_p)]
+
+
+class VerifyParams(C.Structure):
+    _fields_ = [("N", C.c_int32), ("B", C.c_int32), ("V", C.c_int64), ("dtype", C.c_int32), ("reserved", C.c_int32),
+                ("ar_logits", C.c_void_p), ("scaffold_mask", C.c_void_p), ("draft", C.c_void_p), ("mask", C.c_void_p),
+                ("tokens", C.c_void_p), ("n_accepted", C.c_void_p), ("accepted", C.c_void_p),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
 
 class KvUpdateParams(C.Structure):
@@ -77,6 +85,10 @@ def load_library():
         lib.fdd_unmask_workspace.argtypes = [C.POINTER(UnmaskParams)]
         lib.fdd_unmask_step.restype = C.c_int
         lib.fdd_unmask_step.argtypes = [C.POINTER(UnmaskParams)]
+        lib.fdd_verify_workspace.restype = C.c_size_t
+        lib.fdd_verify_workspace.argtypes = [C.POINTER(VerifyParams)]
+        lib.fdd_verify_step.restype = C.c_int
+        lib.fdd_verify_step.argtypes = [C.POINTER(VerifyParams)]
         lib.fdd_fork_block.restype = C.c_int
         lib.fdd_fork_block.argtypes = [C.c_int32, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.fdd_block_kv_update.restype = C.c_int
@@ -145,7 +157,8 @@ def _workspace(ws, need, device):
     return ws, ws.numel() * ws.element_size()
 
 
-def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed=None):
+def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed=None,
+                 causal_block=False):
     N, B, Hq, D = q.shape
     L, Hkv = prefix_k.shape[0], block_k.shape[2]
     if tuple(prefix_k.shape[1:]) != (Hkv, D) or tuple(prefix_v.shape) != tuple(prefix_k.shape):
@@ -167,6 +180,7 @@ def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, sc
     p.out = _dev(out, "out") if out is not None else None
     p.splits = int(splits)
     p.prefix_v_packed = _dev(prefix_v_packed, "prefix_v_packed")
+    p.flags = FDD_ATTN_CAUSAL_BLOCK if causal_block else 0
     return p
 
 
@@ -197,13 +211,15 @@ def fdd_block_attn_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0, 
 
 
 def fdd_block_attn(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask=None, out=None, scale=None,
-                   workspace=None, stream=None, splits=0, prefix_v_packed=None):
-    """out[N,B,Hq,D] = shared-prefix block-causal attention (see include/fdd.h)."""
+                   workspace=None, stream=None, splits=0, prefix_v_packed=None, causal_block=False):
+    """out[N,B,Hq,D] = shared-prefix block-causal attention (see include/fdd.h).
+    ``causal_block=True`` is the verify pass: causal inside the block."""
     import torch
     lib = load_library()
     if out is None:
         out = torch.empty_like(q)
-    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed)
+    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed,
+                     causal_block)
     need = lib.fdd_block_attn_workspace(C.byref(p))
     ws, nbytes = _workspace(workspace, need, q.device)
     p.workspace = ws.data_ptr() if ws is not None else None
@@ -260,6 +276,36 @@ def fdd_unmask_step(logits, mask, scaffold_mask, tau, tokens, confidences=None, 
     p.stream = _stream_ptr(stream)
     _check(lib.fdd_unmask_step(C.byref(p)))
     return tokens, confidences, n_unmasked, committed
+
+
+def fdd_verify_step(ar_logits, mask, scaffold_mask, draft, tokens, n_accepted=None, accepted=None, workspace=None,
+                    stream=None):
+    """Accept scan of scaffold speculative decoding; ``tokens`` and ``mask`` are
+    updated in place.  Returns (tokens, n_accepted, accepted)."""
+    import torch
+    lib = load_library()
+    N, B, V = ar_logits.shape
+    for t, dt, nm in ((mask, torch.uint8, "mask"), (tokens, torch.int32, "tokens"), (draft, torch.int32, "draft")):
+        if t.dtype != dt or tuple(t.shape) != (N, B):
+            raise TypeError(f"{nm} must be {dt} [N,B]")
+    dev = ar_logits.device
+    if n_accepted is None:
+        n_accepted = torch.empty((N,), dtype=torch.int32, device=dev)
+    if accepted is None:
+        accepted = torch.empty((N, B), dtype=torch.uint8, device=dev)
+    p = VerifyParams()
+    p.N, p.B, p.V, p.dtype = N, B, V, _dtype_code(ar_logits)
+    p.ar_logits = _dev(ar_logits, "ar_logits")
+    p.scaffold_mask = _dev(scaffold_mask, "scaffold_mask")
+    p.draft, p.mask, p.tokens = _dev(draft, "draft"), _dev(mask, "mask"), _dev(tokens, "tokens")
+    p.n_accepted, p.accepted = _dev(n_accepted, "n_accepted"), _dev(accepted, "accepted")
+    need = lib.fdd_verify_workspace(C.byref(p))
+    ws, nbytes = _workspace(workspace, need, dev)
+    p.workspace = ws.data_ptr() if ws is not None else None
+    p.workspace_bytes = nbytes
+    p.stream = _stream_ptr(stream)
+    _check(lib.fdd_verify_step(C.byref(p)))
+    return tokens, n_accepted, accepted
 
 
 def fdd_fork_block(src, N, dst=None, stream=None):

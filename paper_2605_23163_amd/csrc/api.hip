@@ -33,7 +33,7 @@ fdd_status check_attn_shape(const fdd_attn_params* p)
     if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_block_attn: dtype %d is neither FDD_F32 nor FDD_BF16", p->dtype);
     if (p->D != 64 && p->D != 128) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: head size D=%d not supported (64 or 128)", p->D);
     if (p->splits < 0 || p->splits > 64) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: splits=%d outside [0, 64]", p->splits);
-    if (p->reserved != 0) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: reserved field must be 0");
+    if (p->flags & ~FDD_ATTN_CAUSAL_BLOCK) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: unknown bits in flags (0x%x)", p->flags);
     if ((long long)p->N * p->B * (p->Hq / p->Hkv) > (1ll << 30) || (long long)p->N * p->B * p->Hq * p->D > (1ll << 40))
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq too large");
     if ((long long)p->L * p->Hkv * p->D * 4 >= (1ll << 31))
@@ -231,6 +231,36 @@ fdd_status fdd_unmask_step(const fdd_unmask_params* p)
     if (p->workspace_bytes < plan.ws_bytes) return fail(FDD_ERR_WORKSPACE, "fdd_unmask_step: workspace has %zu bytes, %zu needed", p->workspace_bytes, plan.ws_bytes);
     hipError_t e = launch_unmask(*p, plan, static_cast<hipStream_t>(p->stream));
     if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_unmask_step: launch failed: %s", hipGetErrorString(e));
+    return FDD_OK;
+}
+
+size_t fdd_verify_workspace(const fdd_verify_params* p)
+{
+    UnmaskPlan plan;
+    if (!p || p->V >= (1ll << 31) || (long long)p->N * p->B > (1ll << 24) ||
+        (p->dtype != FDD_F32 && p->dtype != FDD_BF16) || !make_vocab_plan(p->N, p->B, p->V, p->dtype, &plan))
+        return 0;
+    return plan.ws_bytes;
+}
+
+fdd_status fdd_verify_step(const fdd_verify_params* p)
+{
+    if (!p) return fail(FDD_ERR_NULL, "fdd_verify_step: params is NULL");
+    if (p->N <= 0 || p->B <= 0 || p->V <= 0) return fail(FDD_ERR_SHAPE, "fdd_verify_step: N, B, V must be positive (got N=%d B=%d V=%lld)", p->N, p->B, (long long)p->V);
+    if (p->V >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_verify_step: V must be below 2^31");
+    if ((long long)p->N * p->B > (1ll << 24)) return fail(FDD_ERR_SHAPE, "fdd_verify_step: N*B too large");
+    if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_verify_step: dtype %d is neither FDD_F32 nor FDD_BF16", p->dtype);
+    if (p->reserved != 0) return fail(FDD_ERR_UNSUPPORTED, "fdd_verify_step: reserved field must be 0");
+    if (!p->ar_logits || !p->draft || !p->mask || !p->tokens)
+        return fail(FDD_ERR_NULL, "fdd_verify_step: ar_logits, draft, mask and tokens must not be NULL");
+    if (!aligned16(p->ar_logits)) return fail(FDD_ERR_UNSUPPORTED, "fdd_verify_step: ar_logits must be 16-byte aligned");
+    UnmaskPlan plan;
+    make_vocab_plan(p->N, p->B, p->V, p->dtype, &plan);
+    if (!p->workspace) return fail(FDD_ERR_WORKSPACE, "fdd_verify_step: workspace is NULL, %zu bytes needed", plan.ws_bytes);
+    if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return fail(FDD_ERR_WORKSPACE, "fdd_verify_step: workspace must be 256-byte aligned");
+    if (p->workspace_bytes < plan.ws_bytes) return fail(FDD_ERR_WORKSPACE, "fdd_verify_step: workspace has %zu bytes, %zu needed", p->workspace_bytes, plan.ws_bytes);
+    hipError_t e = launch_verify(*p, plan, static_cast<hipStream_t>(p->stream));
+    if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_verify_step: launch failed: %s", hipGetErrorString(e));
     return FDD_OK;
 }
 

@@ -93,6 +93,7 @@ struct Args {
     int W;          // workgroups
     int max_seg;    // partial slots per M-tile
     int S;          // > 0: every M-tile is cut into S equal pieces (W = Hkv*MT*S); 0: free ranges
+    int causal;     // in-block keys are visible up to the query's own position only
     long long U;    // units in total = Hkv * MT * TPU
     float c;        // scale * log2(e)
 };
@@ -115,6 +116,7 @@ struct Tile {
     const uint16_t* v;
     int valid;
     int rollout;
+    int key0;   // block position of the tile's first key (tail tiles)
 };
 
 template <int D, int WAVES>
@@ -205,6 +207,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     const int nb = row_ok ? row / a.G : 0;           // n*B + b
     const int g = row_ok ? row % a.G : 0;
     const int my_rollout = row_ok ? nb / a.B : -1;
+    const int my_b = row_ok ? nb % a.B : 0;            // position inside the block
     // rollouts spanned by this wave's rows and by the whole M-tile
     const int wave_n_lo = row0 / BG;
     const int wave_n_hi = (min(row0 + 31, a.R - 1)) / BG;
@@ -242,6 +245,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             t.v = a.pv + (size_t)key0 * kv_stride + (size_t)kh * D;
             t.valid = min(KT, a.L - key0);
             t.rollout = -1;
+            t.key0 = 0;
         } else {
             const int j = i - n_prefix;
             const int n = wg_n_lo + j / tail_tiles_per_rollout;
@@ -251,6 +255,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             t.v = a.bv + off;
             t.valid = min(KT, a.B - key0);
             t.rollout = n;
+            t.key0 = key0;
         }
         return t;
     };
@@ -615,7 +620,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int key = kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                    if (!row_sees || key >= t.valid) s[kb][v] = -INFINITY;
+                    const bool later = a.causal && t.rollout >= 0 && t.key0 + key > my_b;   // verify pass: causal inside the block
+                    if (!row_sees || key >= t.valid || later) s[kb][v] = -INFINITY;
                 }
             update_reference(row_max(s[0], s[1]));
             const float mc = ((m_ref == -INFINITY) ? 0.f : m_ref) * a.c;
@@ -757,6 +763,7 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.TPF = p.L / 64;
     a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.U = plan.U; a.S = plan.uniform;
+    a.causal = (p.flags & FDD_ATTN_CAUSAL_BLOCK) ? 1 : 0;
     a.c = scale * 1.4426950408889634f;
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;
     if (plan.packed)

@@ -26,6 +26,7 @@ struct Args {
     float* ws_o;
     float* ws_ml;
     int N, B, L, Hq, Hkv, G, R, MT, TP, S;
+    int causal;   // in-block keys are visible up to the query's own position only
     float c;   // scale * log2(e)
 };
 
@@ -52,6 +53,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
     const int nb = row_ok ? row / a.G : 0;
     const int g = row_ok ? row % a.G : 0;
     const int my_rollout = row_ok ? nb / a.B : -1;
+    const int my_b = row_ok ? nb % a.B : 0;
     const int wg_row_hi = min(mt * RT + RT - 1, a.R - 1);
     const int wg_n_lo = (mt * RT) / BG;
     const int wg_n_hi = wg_row_hi / BG;
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
 
     for (int i = 0; i < n_prefix + n_tail; ++i) {
         const float *kp, *vp;
-        int valid, rollout;
+        int valid, rollout, blk0 = 0;
         if (i < n_prefix) {
             const int key0 = (t0 + i) * KT;
             kp = a.pk + (size_t)key0 * kv_stride + (size_t)kh * D;
@@ -98,6 +100,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
             vp = a.bv + off;
             valid = min(KT, a.B - key0);
             rollout = n;
+            blk0 = key0;
         }
         __syncthreads();   // previous tile fully consumed (and qs written, first time)
         for (int x = tid; x < KT * (D / 4); x += THREADS) {
@@ -129,7 +132,8 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
                 acc = fmaf(qq.z, kk.z, acc);
                 acc = fmaf(qq.w, kk.w, acc);
             }
-            sc[j] = (sees && key < valid) ? acc : -INFINITY;
+            const bool later = a.causal && rollout >= 0 && blk0 + key > my_b;
+            sc[j] = (sees && key < valid && !later) ? acc : -INFINITY;
             mx = fmaxf(mx, sc[j]);
         }
 #pragma unroll
@@ -260,6 +264,7 @@ hipError_t launch_attn_f32(const fdd_attn_params& p, const AttnPlan& plan, float
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.S = plan.splits;
     a.c = scale * 1.4426950408889634f;
+    a.causal = (p.flags & FDD_ATTN_CAUSAL_BLOCK) ? 1 : 0;
     if (plan.mtile_rows != RT) return hipErrorInvalidValue;
     const dim3 grid(plan.MT, plan.splits, p.Hkv);
     if (p.D == 128) hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(THREADS), 0, s, a);

@@ -60,7 +60,9 @@ struct UnmaskPlan {
     size_t ws_bytes;  // [N*B][vsplits] x {float max; int32 arg; float sum; int32 pad}
 };
 bool make_unmask_plan(const fdd_unmask_params& p, UnmaskPlan* plan);
+bool make_vocab_plan(int N, int B, long long V, int dtype, UnmaskPlan* plan);
 hipError_t launch_unmask(const fdd_unmask_params& p, const UnmaskPlan& plan, hipStream_t s);
+hipError_t launch_verify(const fdd_verify_params& p, const UnmaskPlan& plan, hipStream_t s);
 
 hipError_t launch_fork_block(int N, size_t bytes, const void* src, void* dst, hipStream_t s);
 hipError_t launch_kv_update(const fdd_kv_update_params& p, hipStream_t s);

@@ -54,6 +54,7 @@ struct Args {
     int32_t* n_unmasked;
     uint8_t* committed;
     Partial* ws;
+    const int32_t* draft;   // verify pass only
     int N, B, vsplits;
     long long V;
     float tau;
@@ -270,10 +271,60 @@ __global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
     }
 }
 
+// Accept scan of scaffold speculative decoding: one wavefront per rollout.
+// Draft positions are visited in ascending order; drafts equal to the AR arg
+// max are accepted up to the first mismatch, which takes the AR token; later
+// drafts are left masked.
+__global__ __launch_bounds__(STHREADS) void verify_scan_kernel(Args a)
+{
+    const int n = blockIdx.x;
+    const int tid = threadIdx.x;
+    auto ar_token = [&](size_t i) {
+        const Partial* p = a.ws + i * a.vsplits;
+        float M = p[0].m;
+        int arg = p[0].arg;
+        for (int s = 1; s < a.vsplits; ++s)
+            if (p[s].m > M) { M = p[s].m; arg = p[s].arg; }   // ascending pieces: lowest id on ties
+        return arg;
+    };
+    // pass 1: position of the first mismatch
+    int first_bad = 0x7fffffff;
+    for (int b = tid; b < a.B; b += STHREADS) {
+        const size_t i = (size_t)n * a.B + b;
+        const bool is_draft = a.mask[i] == 1 && !(a.scaffold && a.scaffold[i]);
+        if (is_draft && ar_token(i) != a.draft[i] && b < first_bad) first_bad = b;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) first_bad = min(first_bad, __shfl_xor(first_bad, off, 64));
+    // pass 2: accept up to it, replace at it, leave the rest
+    int count = 0;
+    for (int b = tid; b < a.B; b += STHREADS) {
+        const size_t i = (size_t)n * a.B + b;
+        const bool is_draft = a.mask[i] == 1 && !(a.scaffold && a.scaffold[i]);
+        uint8_t acc = 0;
+        if (is_draft && b <= first_bad) {
+            acc = (b == first_bad) ? 2 : 1;
+            a.tokens[i] = (b == first_bad) ? ar_token(i) : a.draft[i];
+            a.mask[i] = 0;
+            ++count;
+        }
+        if (a.committed) a.committed[i] = acc;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) count += __shfl_xor(count, off, 64);
+    if (tid == 0 && a.n_unmasked) a.n_unmasked[n] = count;
+}
+
 }  // namespace
 
 bool make_unmask_plan(const fdd_unmask_params& p, UnmaskPlan* plan)
 {
+    return make_vocab_plan(p.N, p.B, p.V, p.dtype, plan);
+}
+
+bool make_vocab_plan(int N, int B, long long V, int dtype, UnmaskPlan* plan)
+{
+    struct { int N, B; long long V; int dtype; } p = {N, B, V, dtype};
     if (p.N <= 0 || p.B <= 0 || p.V <= 0) return false;
     const long long rows = (long long)p.N * p.B;
     const long long es = p.dtype == FDD_BF16 ? 2 : 4;
@@ -299,6 +350,7 @@ hipError_t launch_unmask(const fdd_unmask_params& p, const UnmaskPlan& plan, hip
     a.n_unmasked = p.n_unmasked;
     a.committed = p.committed;
     a.ws = static_cast<Partial*>(p.workspace);
+    a.draft = nullptr;
     a.N = p.N; a.B = p.B; a.vsplits = plan.vsplits; a.V = p.V; a.tau = p.tau;
     const dim3 grid((unsigned)(plan.vsplits * p.N * p.B));
     if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_reduce_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
@@ -306,6 +358,28 @@ hipError_t launch_unmask(const fdd_unmask_params& p, const UnmaskPlan& plan, hip
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(block_select_kernel, dim3(p.N), dim3(STHREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify(const fdd_verify_params& p, const UnmaskPlan& plan, hipStream_t s)
+{
+    Args a;
+    a.logits = p.ar_logits;
+    a.scaffold = p.scaffold_mask;
+    a.mask = p.mask;
+    a.tokens = p.tokens;
+    a.conf = nullptr;
+    a.n_unmasked = p.n_accepted;
+    a.committed = p.accepted;
+    a.ws = static_cast<Partial*>(p.workspace);
+    a.draft = p.draft;
+    a.N = p.N; a.B = p.B; a.vsplits = plan.vsplits; a.V = p.V; a.tau = 0.f;
+    const dim3 grid((unsigned)(plan.vsplits * p.N * p.B));
+    if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_reduce_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
+    else hipLaunchKernelGGL(vocab_reduce_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(verify_scan_kernel, dim3(p.N), dim3(STHREADS), 0, s, a);
     return hipGetLastError();
 }
 

@@ -61,7 +61,7 @@ def test_attn_workspace_is_host_arithmetic(lib):
 
 @pytest.mark.parametrize("kw,code", [
     (dict(N=0), 2), (dict(B=-1), 2), (dict(L=-1), 2), (dict(Hq=30), 2), (dict(dtype=7), 3), (dict(D=96), 4),
-    (dict(splits=65), 4), (dict(reserved=1), 4), (dict(q=None), 1), (dict(out=None), 1), (dict(prefix_k=None), 1),
+    (dict(splits=65), 4), (dict(flags=2), 4), (dict(q=None), 1), (dict(out=None), 1), (dict(prefix_k=None), 1),
     (dict(block_v=None), 1), (dict(q=264), 4), (dict(out=256), 4), (dict(workspace=None), 5),
     (dict(workspace=4100), 5), (dict(workspace_bytes=16), 5), (dict(scale=float("nan")), 4),
 ])
@@ -105,6 +105,24 @@ def test_prefix_pack_sizes_and_errors(lib):
     assert lib.fdd_prefix_pack(256, 4096, 0, 128, bd.FDD_BF16, 512, 1 << 30, None) == 2
     assert lib.fdd_prefix_pack(256, 10, 4, 128, bd.FDD_BF16, None, 0, None) == 0       # nothing to pack
     assert lib.fdd_last_error().decode().startswith("fdd_prefix_pack:")
+
+
+def test_verify_workspace_and_errors(lib):
+    def vp(**kw):
+        p = bd.VerifyParams()
+        base = dict(N=8, B=32, V=152064, dtype=bd.FDD_BF16, ar_logits=256, draft=512, mask=768, tokens=1024,
+                    workspace=4096, workspace_bytes=1 << 30)
+        base.update(kw)
+        for k, v in base.items():
+            setattr(p, k, v)
+        return p
+    assert lib.fdd_verify_workspace(C.byref(vp())) == lib.fdd_unmask_workspace(C.byref(unmask()))
+    assert lib.fdd_verify_workspace(C.byref(vp(V=0))) == 0
+    for kw, code in [(dict(N=0), 2), (dict(V=1 << 31), 2), (dict(dtype=5), 3), (dict(reserved=1), 4), (dict(draft=None), 1),
+                     (dict(ar_logits=None), 1), (dict(ar_logits=264), 4), (dict(workspace=None), 5), (dict(workspace_bytes=1), 5)]:
+        assert lib.fdd_verify_step(C.byref(vp(**kw))) == code, kw
+        assert lib.fdd_last_error().decode().startswith("fdd_verify_step:")
+    assert lib.fdd_verify_step(None) == 1
 
 
 def test_bookkeeping_errors(lib):
