@@ -119,6 +119,71 @@ def time_attention_only(F, w, steps, warmup, n_buffers):
     }
 
 
+def time_spec_verify(F, w, d, g, logits, steps, warmup):
+    """Verify pass of scaffold speculative decoding at the bench workload:
+    causal in-block attention, then the accept scan over the AR logits.  The
+    mask state is restored by a fork before every pass (inside the timing)."""
+    import torch
+    scaffold = dev(d["scaffold_mask"])
+    parent = {k: dev(d[k][0]) for k in ("block_k", "block_v", "tokens", "mask")}
+    st = {k: torch.empty((w.N,) + tuple(parent[k].shape), dtype=parent[k].dtype, device="cuda") for k in parent}
+    rng = np.random.default_rng([w.seed, 77])
+    draft = dev(rng.integers(0, w.V, size=(w.N, w.B)).astype(np.int32))
+    out = torch.empty_like(g["q"])
+    nacc = torch.empty((w.N,), dtype=torch.int32, device="cuda")
+    acc = torch.empty((w.N, w.B), dtype=torch.uint8, device="cuda")
+    packed_v = F.fdd_prefix_pack(g["prefix_v"])
+    ws_a = torch.empty(max(256, F.fdd_block_attn_workspace(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"],
+                                                           st["block_v"], prefix_v_packed=packed_v)),
+                       dtype=torch.uint8, device="cuda")
+    ws_u = torch.empty(max(256, F.fdd_unmask_workspace(logits[0])), dtype=torch.uint8, device="cuda")
+    ev = Events(steps)
+    v0 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    v1 = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+
+    def one(i, timed):
+        for k in ("tokens", "mask"):
+            F.fdd_fork_block(parent[k], w.N, dst=st[k])
+        if timed:
+            F.fdd_profile_attn_events(*ev.pairs[i])
+        F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"], scaffold, out=out,
+                         workspace=ws_a, prefix_v_packed=packed_v, causal_block=True)
+        if timed:
+            v0[i].record()
+        F.fdd_verify_step(logits[i % 2], st["mask"], scaffold, draft, st["tokens"], nacc, acc, workspace=ws_u)
+        if timed:
+            v1[i].record()
+
+    for k in ("block_k", "block_v"):
+        F.fdd_fork_block(parent[k], w.N, dst=st[k])
+    for i in range(warmup):
+        one(i, False)
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for i in range(steps):
+        one(i, True)
+    t1.record()
+    torch.cuda.synchronize()
+    F.fdd_profile_attn_events(None, None)
+    ms = t0.elapsed_time(t1) / steps
+    attn_ms = ev.mean_ms(steps)
+    ver_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(v0, v1)]))
+    elig = int(((d["mask"][0] == 1) & (d["scaffold_mask"][0] == 0)).sum()) * w.N
+    byt = elig * w.V * 2
+    # causal tail: position b sees L + b + 1 keys
+    flops = 4.0 * w.N * w.Hq * w.D * sum(w.L + b + 1 for b in range(w.B))
+    return {
+        "workload": f"{w.name}: causal in-block attention + accept scan, N={w.N} B={w.B} L={w.L} V={w.V} bf16",
+        "pass_us": round(ms * 1e3, 2), "rollout_tokens_per_s": round(w.N * w.B / (ms * 1e-3), 1),
+        "attn_kernel_us": round(attn_ms * 1e3, 2), "attn_tflops": round(flops / (attn_ms * 1e-3) / 1e12, 1),
+        "attn_frac_peak_mfma": round(flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "verify_call_us": round(ver_ms * 1e3, 2), "verify_rows": elig,
+        "verify_GBs": round(byt / (ver_ms * 1e-3) / 1e9, 1),
+        "verify_frac_peak_hbm": round(byt / (ver_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+    }
+
+
 def cpu_baseline(w, d, logits):
     """The fp64 oracle as it stands on a bounded sample of one step."""
     import oracle
@@ -276,6 +341,8 @@ def main():
         res["n1_prefix_stream"] = time_attention_only(F, n1, 400, 40, 128)
         n1_long = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
         res["n1_prefix_stream_L16384"] = time_attention_only(F, n1_long, 200, 20, 20)
+        if has_unmask:
+            res["spec_verify"] = time_spec_verify(F, w, d, g, logits, 100, 10)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, logits_h)
     print(json.dumps(res))

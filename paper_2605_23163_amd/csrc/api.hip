@@ -38,6 +38,14 @@ fdd_status check_attn_shape(const fdd_attn_params* p)
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq too large");
     if ((long long)p->L * p->Hkv * p->D * 4 >= (1ll << 31))
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: prefix K (L*Hkv*D elements) must stay below 2 GiB");
+    if ((long long)p->N * p->B * p->Hkv * p->D * 4 >= (1ll << 32))
+        return fail(FDD_ERR_SHAPE, "fdd_block_attn: block K (N*B*Hkv*D elements) must stay below 4 GiB");
+    {
+        // work units of the bf16 path: (KV head, 256-row M-tile, 64-key prefix tile)
+        const long long mt = ((long long)p->N * p->B * (p->Hq / p->Hkv) + 255) / 256;
+        const long long tpu = p->L > 0 ? (p->L + 63) / 64 : 1;
+        if (p->Hkv * mt * tpu >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq*L too large");
+    }
     if (std::isnan(p->scale) || std::isinf(p->scale)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: scale is not finite");
     return FDD_OK;
 }

@@ -75,6 +75,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
 constexpr int KT = 64;           // keys per tile
+constexpr int NB = 4;            // ring slots per operand in LDS
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 
 struct Args {
@@ -91,52 +92,28 @@ struct Args {
     int TPF;        // full prefix tiles = L / 64
     int TPU;        // units per M-tile = max(TP, 1)
     int W;          // workgroups
+    int per_xcd;    // ceil(W / 8)
     int max_seg;    // partial slots per M-tile
     int S;          // > 0: every M-tile is cut into S equal pieces (W = Hkv*MT*S); 0: free ranges
+    int base, rem;  // free ranges: U / W and U % W
     int causal;     // in-block keys are visible up to the query's own position only
-    long long U;    // units in total = Hkv * MT * TPU
     float c;        // scale * log2(e)
-};
-
-// Segments of M-tile M: the workgroups whose unit range [U w / W, U (w+1) / W)
-// meets [M TPU, (M+1) TPU).
-__host__ __device__ inline int first_wg_of(long long M, const int TPU, const int W, const long long U)
-{
-    return (int)(((M * TPU + 1) * W + U - 1) / U) - 1;
-}
-__host__ __device__ inline int last_wg_of(long long M, const int TPU, const int W, const long long U)
-{
-    return (int)(((M + 1) * TPU * W + U - 1) / U) - 1;
-}
-
-// One 64-key tile of K and V to stream: where it starts, how many of its
-// keys exist, and which rollout's rows may see it (-1: every row).
-struct Tile {
-    const uint16_t* k;
-    const uint16_t* v;
-    int valid;
-    int rollout;
-    int key0;   // block position of the tile's first key (tail tiles)
 };
 
 template <int D, int WAVES>
 struct Cfg {
     static constexpr int THREADS = WAVES * 64;
-    static constexpr int KROW = D * 2 + 16;             // bytes per K row in LDS
-    static constexpr int VROW = D * 2 + 64;             // bytes per V row in LDS
-    static constexpr int K_BYTES = KT * KROW;
-    static constexpr int V_BYTES = KT * VROW;
-    static constexpr int BUF_BYTES = K_BYTES + V_BYTES;
-    static constexpr int K_CHUNKS = KT * (D / 8);        // 16-byte pieces of a K tile
-    static constexpr int K_PER_THREAD = K_CHUNKS / THREADS;
-    static_assert(K_CHUNKS % THREADS == 0, "tile must divide over the workgroup");
-    // direct-to-LDS path: unpadded 64 x D tiles moved in 1 KB pieces, one per wavefront instruction
+    // 64 x D tiles, unpadded, moved global -> LDS in 1 KB pieces, one per wavefront instruction
     static constexpr int T_BYTES = KT * D * 2;
-    static constexpr int NI = T_BYTES / 1024 / WAVES;    // pieces per wavefront
-    static constexpr int CH = D / 8;                     // 16-byte pieces per K row
-    static constexpr int RPB = 1024 / (D * 2);           // K rows per 1 KB piece
-    static constexpr int RPL = 256 / (D * 2);            // K rows per 256-byte bank line
+    static constexpr int NI = T_BYTES / 1024 / WAVES;    // pieces per wavefront and tile
+    static constexpr int IPT = 2 * NI;                   // load instructions per wavefront for K and V of one tile
+    static constexpr int CH = D / 8;                     // 16-byte pieces per row
+    static constexpr int RPB = 1024 / (D * 2);           // rows per 1 KB piece
+    static constexpr int RPL = 256 / (D * 2);            // rows per 256-byte bank line
+    static constexpr int V_RING = NB * T_BYTES;          // LDS offset of the V ring (the K ring starts at 0)
+    static constexpr int LDS_BYTES = 2 * NB * T_BYTES;
     static_assert(NI >= 1 && T_BYTES % (1024 * WAVES) == 0, "tile must divide over the wavefronts");
+    static_assert(3 * IPT < 64, "outstanding loads must fit the counter");
 };
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -149,6 +126,20 @@ __device__ __forceinline__ float other_half(float x)
     const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     return __builtin_bit_cast(float, (threadIdx.x & 32) ? r[0] : r[1]);
 }
+
+// Wait until at most N of this wavefront's vector memory operations are
+// still in flight (they complete in issue order).
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    static_assert(N >= 0 && N < 64, "counter range");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+// Workgroup barrier that orders LDS traffic only.  (__syncthreads() also
+// fences global memory, which makes the compiler drain every tile still on
+// its way into the ring.)  No memory access is moved across it.
+__device__ __forceinline__ void wg_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
 // Nothing is scheduled across this point: the source order of the pieces it
 // separates is the order the hardware sees.
@@ -165,509 +156,545 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     constexpr int KS = D / 16;   // MFMA k-steps of Q K^T
     constexpr int DB = D / 32;   // 32-channel blocks of the output
     constexpr int MROWS = WAVES * 32;
+    constexpr uint32_t RSRC_FLAGS = 0x00020000;
 
     extern __shared__ __align__(16) unsigned char lds[];
+    typedef __attribute__((address_space(3))) void lds_void;
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int lane = tid & 63;
     const int l32 = lane & 31;
     const int half = lane >> 5;
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // same value, known to be wave-uniform
 
-    // ---- stream-K: this workgroup's contiguous range of (M-tile, prefix tile) units
-    // Workgroups are dealt to the 8 XCDs round-robin by their launch index.
-    // Ranges are numbered so that the workgroups of one XCD own neighbouring
-    // ranges.
-    const int per_xcd = (a.W + kNumXCD - 1) / kNumXCD;
-    int wg = (int)(blockIdx.x % kNumXCD) * per_xcd + (int)(blockIdx.x / kNumXCD);
+    // ---- this workgroup's share of the (M-tile, prefix tile) units ------------
+    // Workgroups are dealt to the 8 XCDs round-robin by their launch index;
+    // ranges are numbered so that the workgroups of one XCD own neighbours.
+    int wg = (int)(blockIdx.x % kNumXCD) * a.per_xcd + (int)(blockIdx.x / kNumXCD);
     if (wg >= a.W) return;
+    int M, t_begin, todo, piece = 0;
     if (a.S > 0) {
         // equal pieces: neighbours are the M-tiles of one (KV head, piece), which
         // walk the same keys in step, so each XCD fetches its share of K/V once
-        const int mt_ = wg % a.MT, piece = (wg / a.MT) % a.S, kh_ = wg / (a.MT * a.S);
-        wg = (kh_ * a.MT + mt_) * a.S + piece;
+        const int mt_ = wg % a.MT, rest = wg / a.MT;
+        piece = rest % a.S;
+        M = (rest / a.S) * a.MT + mt_;
+        t_begin = a.TPU * piece / a.S;
+        todo = a.TPU * (piece + 1) / a.S - t_begin;
+    } else {
+        const int u0 = unit_begin(wg, a.base, a.rem);
+        todo = unit_begin(wg + 1, a.base, a.rem) - u0;
+        M = u0 / a.TPU;
+        t_begin = u0 - M * a.TPU;
     }
-    const long long u_end = a.U * (wg + 1) / a.W;
-    for (long long u_cur = a.U * wg / a.W; u_cur < u_end;) {
-    const int M = (int)(u_cur / a.TPU);              // M-tile index over all KV heads
-    const int t_begin = (int)(u_cur % a.TPU);
-    const int t_end = (int)min((long long)a.TPU, t_begin + (u_end - u_cur));
-    u_cur += t_end - t_begin;
-    const int kh = M / a.MT;
-    const int mt = M % a.MT;
-    const int seg_first = first_wg_of(M, a.TPU, a.W, a.U);
-    const int n_seg = last_wg_of(M, a.TPU, a.W, a.U) - seg_first + 1;
-    const int seg = wg - seg_first;
 
-    const int BG = a.B * a.G;
-    const int row0_wg = mt * MROWS;
-    const int row0 = row0_wg + wave * 32;
-    const int row = row0 + l32;
-    const bool row_ok = row < a.R;
-    const int nb = row_ok ? row / a.G : 0;           // n*B + b
-    const int g = row_ok ? row % a.G : 0;
-    const int my_rollout = row_ok ? nb / a.B : -1;
-    const int my_b = row_ok ? nb % a.B : 0;            // position inside the block
-    // rollouts spanned by this wave's rows and by the whole M-tile
-    const int wave_n_lo = row0 / BG;
-    const int wave_n_hi = (min(row0 + 31, a.R - 1)) / BG;
-    const bool wave_has_rows = row0 < a.R;
-    const int wg_n_lo = row0_wg / BG;
-    const int wg_n_hi = (min(row0_wg + MROWS - 1, a.R - 1)) / BG;
-
-    // ---- Q fragments: B operand of S^T = K Q^T ------------------------------
-    // (loaded after the first K/V tiles have been requested, so the two latencies overlap)
-    bf16x8 qf[KS];
-    auto load_q = [&]() {
-        const uint16_t* qp = a.q + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D + half * 8;
+    // ---- per-lane constants of the tile movement and of the fragment reads ------
+    const uint32_t stride2 = (uint32_t)(a.Hkv * D * 2);       // bytes between consecutive keys
+    // K fragment of k-step ks: row l32 of a 32-key block, 16-byte piece (2 ks + half)
+    // at its swizzled place, which is the place of k-step 0 with ks XORed in
+    const uint32_t k_fragoff0 = (uint32_t)(l32 * D * 2 + ((((l32 / C::RPL) & (C::CH - 1)) ^ half) << 4));
+    const uint32_t v_fragoff = (uint32_t)(half * (D * 16) + l32 * 16);   // packed V^T: [16-key step][half][d][8 keys]
+    // Unpacked V, transposing reads.  In a 16-lane group, lane 4j+q points at 4
+    // channels of key row j; the read returns to lane i the 4 keys of channel i.
+    // Element e of the assembled fragment is key 16 t4 + 8 (e/4) + 4 half + e%4,
+    // the key order of the probabilities in the S^T accumulator.  Channel block
+    // db sits at the swizzled place of block 0 with db XORed in.
+    uint32_t vtr_off0;
+    {
+        const int row_l = half * 4 + ((lane & 15) >> 2);
+        const int x = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+        const int sw = (((row_l / C::RPL) & 3) << 2) & (C::CH - 1);
+        vtr_off0 = (uint32_t)(row_l * D * 2 + ((x ^ sw) << 4) + (lane & 1) * 8);
+    }
+    // Tile movement: piece jn of this wavefront covers rows (wave NI + jn) RPB .. of
+    // a tile; this lane moves the 16 bytes that land at LDS piece (lane % CH) of
+    // its row.  K: the pieces of a row are XOR-swizzled by the row's bank line.
+    // V as it lies in memory: 32-byte columns are XOR-swizzled by the row, for
+    // the transposing reads.  Packed V^T tiles are copied as they are.
+    uint32_t k_voff[C::NI];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u32x4 raw = {0u, 0u, 0u, 0u};
-            if (row_ok) raw = *reinterpret_cast<const u32x4*>(qp + ks * 16);
-            qf[ks] = __builtin_bit_cast(bf16x8, raw);
-        }
+    for (int jn = 0; jn < C::NI; ++jn) {
+        const int r = (wave * C::NI + jn) * C::RPB + lane / C::CH;
+        k_voff[jn] = (uint32_t)r * stride2 + (uint32_t)(((lane % C::CH) ^ ((r / C::RPL) & (C::CH - 1))) * 16);
+    }
+    const uint32_t vp_voff = (uint32_t)(wave * C::NI * 1024 + lane * 16);
+    const __amdgpu_buffer_rsrc_t pk_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.pk), 0, (uint32_t)a.L * stride2, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t pv_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.pv), 0, (uint32_t)a.L * stride2, RSRC_FLAGS);
+    const __amdgpu_buffer_rsrc_t vt_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.vt), 0, (uint32_t)(a.Hkv * a.TPF) * C::T_BYTES, RSRC_FLAGS);
+
+    auto k_frag = [&](uint32_t kbase, int kb, int ks) -> bf16x8 {
+        return *reinterpret_cast<const bf16x8*>(lds + ((kbase + k_fragoff0) ^ (uint32_t)(ks << 5)) + kb * 32 * D * 2);
     };
-
-    // ---- tile schedule -------------------------------------------------------
-    const int t0 = min(t_begin, a.TP);
-    const int n_prefix = min(t_end, a.TP) - t0;
-    const int tail_tiles_per_rollout = (a.B + KT - 1) / KT;
-    // the segment that ends the M-tile's key range also takes the in-block tail
-    const int n_tail = (t_end == a.TPU) ? (wg_n_hi - wg_n_lo + 1) * tail_tiles_per_rollout : 0;
-    const int n_tiles = n_prefix + n_tail;
-    const size_t kv_stride = (size_t)a.Hkv * D;       // elements between consecutive keys
-
-    auto tile_at = [&](int i) -> Tile {
-        Tile t;
-        if (i < n_prefix) {
-            const int key0 = (t0 + i) * KT;
-            t.k = a.pk + (size_t)key0 * kv_stride + (size_t)kh * D;
-            t.v = a.pv + (size_t)key0 * kv_stride + (size_t)kh * D;
-            t.valid = min(KT, a.L - key0);
-            t.rollout = -1;
-            t.key0 = 0;
-        } else {
-            const int j = i - n_prefix;
-            const int n = wg_n_lo + j / tail_tiles_per_rollout;
-            const int key0 = (j % tail_tiles_per_rollout) * KT;
-            const size_t off = ((size_t)n * a.B + key0) * kv_stride + (size_t)kh * D;
-            t.k = a.bk + off;
-            t.v = a.bv + off;
-            t.valid = min(KT, a.B - key0);
-            t.rollout = n;
-            t.key0 = key0;
-        }
-        return t;
-    };
-
-    // ---- global -> register staging of one tile -----------------------------
-    u32x4 kreg[C::K_PER_THREAD];
-    u32x4 vreg[C::K_PER_THREAD];
-
-    // 16-byte pieces, consecutive lanes along a row; rows beyond `valid` are zero.
-    auto load_rows = [&](u32x4 (&reg)[C::K_PER_THREAD], const uint16_t* base, int valid, bool full) {
-#pragma unroll
-        for (int i = 0; i < C::K_PER_THREAD; ++i) {
-            const int c = tid + i * C::THREADS;
-            const int key = c / (D / 8);
-            const int col = c % (D / 8);
-            u32x4 x = {0u, 0u, 0u, 0u};
-            if (full || key < valid) x = *reinterpret_cast<const u32x4*>(base + (size_t)key * kv_stride + col * 8);
-            reg[i] = x;
-        }
-    };
-    auto store_rows = [&](const u32x4 (&reg)[C::K_PER_THREAD], unsigned char* tile, int row_bytes) {
-#pragma unroll
-        for (int i = 0; i < C::K_PER_THREAD; ++i) {
-            const int c = tid + i * C::THREADS;
-            const int key = c / (D / 8);
-            const int col = c % (D / 8);
-            *reinterpret_cast<u32x4*>(tile + key * row_bytes + col * 16) = reg[i];
-        }
-    };
-    auto load_k = [&](const uint16_t* kp, int valid, bool full) { load_rows(kreg, kp, valid, full); };
-    auto load_v = [&](const uint16_t* vp, int valid, bool full) { load_rows(vreg, vp, valid, full); };
-    auto store_k = [&](int buf) { store_rows(kreg, lds + buf * C::K_BYTES, C::KROW); };
-    auto store_v = [&](int buf) { store_rows(vreg, lds + 2 * C::K_BYTES + buf * C::V_BYTES, C::VROW); };
-
-    // V^T fragment of one P V MFMA (16-key step t4, channel block db) by two
-    // transpose reads.  In a 16-lane group, lane 4j+q points at 4 channels of
-    // key row j; the read returns to lane i the 4 keys of channel i.  Element
-    // e of the fragment is key 16 t4 + 8 (e/4) + 4 half + e%4, the key order of
-    // the probabilities in the S^T accumulator.
-    const int tr_lane_off = ((half * 4 + ((lane & 15) >> 2)) * C::VROW) + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
-    auto v_frag = [&](const unsigned char* vtile, int t4, int db) -> bf16x8 {
+    // `vaddr` = slot base + vtr_off0
+    auto v_frag_tr_at = [&](uint32_t vaddr, int t4, int db) -> bf16x8 {
         typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
-        const unsigned char* p0 = vtile + tr_lane_off + (t4 * 16) * C::VROW + db * 64;
+        const unsigned char* p0 = lds + (vaddr ^ (uint32_t)(db << 6)) + t4 * 16 * (D * 2);
         const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0));
-        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0 + 8 * C::VROW));
+        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(p0 + 8 * (D * 2)));
         typedef short i16x8 __attribute__((ext_vector_type(8)));
         const i16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
         return __builtin_bit_cast(bf16x8, both);
     };
 
-    // ---- streaming-softmax state: one query row per lane --------------------
-    f32x16 o[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
-    float m_ref = -INFINITY;   // reference value the exponentials are taken against (raw score units)
-    float l_run = 0.f;         // this lane's share of the running sum
+    // (wave-uniform values are marked as such, so that addresses built from them stay in scalar registers)
+    M = __builtin_amdgcn_readfirstlane(M);
+    t_begin = __builtin_amdgcn_readfirstlane(t_begin);
+    todo = __builtin_amdgcn_readfirstlane(todo);
+    for (; todo > 0; ++M, t_begin = 0) {
+        const int t_end = min(a.TPU, t_begin + todo);
+        todo -= t_end - t_begin;
+        const int kh = M / a.MT;
+        const int mt = M - kh * a.MT;
+        // stores of the previous segment are out of the way of the load counting below
+        wait_vm<0>();
 
-    // scores of one 32-key block: S^T[key, row] = K[key, :] . Q[row, :]
-    auto qk_block = [&](const unsigned char* kl, int kb, f32x16& s) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kl + (kb * 32 + l32) * C::KROW + ks * 32 + half * 16);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s, 0, 0, 0);
-        }
-    };
-    // maximum of a row's 64 scores (both halves of the wavefront agree on it)
-    auto row_max = [&](const f32x16& s0, const f32x16& s1) -> float {
-        float mx = fmaxf(s0[0], s1[0]);
-#pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, fmaxf(s0[v], s1[v]));
-        return fmaxf(mx, other_half(mx));
-    };
-    // raise the reference when the tile maximum outgrew it by more than 2^8
-    auto update_reference = [&](float mx) {
-        // also true for the first tile (m_ref = -inf); never evaluates inf - inf
-        const bool need = (mx > m_ref) && ((mx - m_ref) * a.c > 8.f);
-        if (__any(need)) {
-            const float m_new = fmaxf(m_ref, mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2((m_ref - m_use) * a.c);
-            l_run *= alpha;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-            m_ref = m_new;
-        }
-    };
-    // probabilities of one 32-key block, rounded to bf16 as two MFMA B operands
-    auto exp_block = [&](const f32x16& s, float mc, bf16x8& p0, bf16x8& p1) {
-        float acc = 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const float p = fast_exp2(fmaf(s[v], a.c, -mc));
-            acc += p;
-            if (v < 8) p0[v] = (__bf16)p; else p1[v - 8] = (__bf16)p;
-        }
-        l_run += acc;
-    };
-    // O^T += V^T P^T for the two 16-key steps of one 32-key block
-    auto pv_block = [&](const unsigned char* vtile, int kb, const bf16x8& p0, const bf16x8& p1) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const bf16x8 vf = v_frag(vtile, kb * 2 + u, db);
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, u == 0 ? p0 : p1, o[db], 0, 0, 0);
-            }
-    };
+        // ---- tile schedule ---------------------------------------------------
+        // Tiles 0 .. F-1 are full 64-key prefix tiles; the rest are masked: the
+        // ragged last prefix tile, then, if this segment ends the M-tile's key
+        // range, the in-block tail of every rollout the M-tile's rows belong to.
+        const int t0 = min(t_begin, a.TP);
+        const int n_prefix = min(t_end, a.TP) - t0;
+        const int F = (n_prefix > 0 && (t0 + n_prefix) * KT > a.L) ? n_prefix - 1 : n_prefix;
 
-    // ---- fast path: full prefix tiles, software pipelined ---------------------
-    // F leading tiles of this piece are complete 64-key prefix tiles.
-    const int F = (n_prefix > 0 && (t0 + n_prefix) * KT > a.L) ? n_prefix - 1 : n_prefix;
-    const uint16_t* pk0 = a.pk + (size_t)t0 * KT * kv_stride + (size_t)kh * D;
-    const uint16_t* pv0 = a.pv + (size_t)t0 * KT * kv_stride + (size_t)kh * D;
-    const size_t tile_elems = (size_t)KT * kv_stride;
-    // LDS: two K buffers then two V buffers (padded register-staged layout or unpadded direct layout)
-    constexpr int KB_BYTES = PACKED ? C::T_BYTES : C::K_BYTES;
-    constexpr int VB_BYTES = PACKED ? C::T_BYTES : C::V_BYTES;
-    unsigned char* const kbuf0 = lds;
-    unsigned char* const vbuf0 = lds + 2 * KB_BYTES;
-    bf16x8 p[4];      // probabilities of a tile as MFMA B operands, one per 16-key step
-
-    // direct path: per-lane byte offsets of the pieces this lane moves, and of
-    // the fragments it reads
-    typedef __attribute__((address_space(3))) void lds_void;
-    __amdgpu_buffer_rsrc_t k_rsrc, v_rsrc;
-    uint32_t k_voff[C::NI], v_voff[C::NI], k_fragoff[KS];
-    const uint32_t v_fragoff = (uint32_t)(half * (D * 16) + l32 * 16);   // packed V^T: [16-key step][half][d][8 keys]
-    const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // same value, known to be wave-uniform
-    if (PACKED) {
-        k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.pk), 0, a.L * a.Hkv * D * 2, 0x00020000);
-        v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.vt), 0, a.Hkv * a.TPF * C::T_BYTES, 0x00020000);
+        // ---- tile j: global memory -> ring slot j % NB, no registers in between ----
+        int issued = 0;
+        // full prefix tile (j < F): offsets were prepared once, only the scalar tile offset changes
+        auto fetch_full = [&](int j) {
+            const uint32_t slot = (uint32_t)(j & (NB - 1)) * C::T_BYTES;
+            const uint32_t soff = (uint32_t)((t0 + j) * KT) * stride2 + (uint32_t)(kh * D * 2);
+            unsigned char* const kdst = lds + slot + wave_u * (C::NI * 1024);
+            unsigned char* const vdst = kdst + C::V_RING;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(pk_rsrc, (lds_void*)kdst, 16, k_voff[0], soff, 0, 0);
+            if (C::NI > 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(pk_rsrc, (lds_void*)(kdst + 1024), 16, k_voff[C::NI - 1], soff, 0, 0);
+            if (PACKED) {
+                const uint32_t voff = (uint32_t)(kh * a.TPF + t0 + j) * C::T_BYTES;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(vt_rsrc, (lds_void*)vdst, 16, vp_voff, voff, 0, 0);
+                if (C::NI > 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(vt_rsrc, (lds_void*)(vdst + 1024), 16, vp_voff + 1024, voff, 0, 0);
+            } else {
+                int tid_f = tid;
+                FDD_PIN(tid_f);     // recomputed at every fetch rather than kept in registers
 #pragma unroll
-        for (int j = 0; j < C::NI; ++j) {
-            const int piece = wave * C::NI + j;
-            const int r = piece * C::RPB + lane / C::CH;          // key row of this lane's 16 bytes
-            const int c = (lane % C::CH) ^ ((r / C::RPL) & (C::CH - 1));   // which piece of the row lands here
-            k_voff[j] = (uint32_t)(r * (int)kv_stride * 2 + c * 16);
-            v_voff[j] = (uint32_t)(piece * 1024 + lane * 16);
-        }
-        const int y = ((l32 / C::RPL) & (C::CH - 1)) ^ half;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) k_fragoff[ks] = (uint32_t)(l32 * D * 2 + (((2 * ks) ^ y) << 4));
-    }
-    // start moving prefix tile `t` (index inside this segment) into buffer `buf`
-    auto fetch_k = [&](int t, int buf) {
-        if (PACKED) {
-            const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)(((size_t)(t0 + t) * KT * kv_stride + (size_t)kh * D) * 2));
-#pragma unroll
-            for (int j = 0; j < C::NI; ++j)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lds_void*)(kbuf0 + buf * KB_BYTES + (wave_u * C::NI + j) * 1024),
-                                                         16, k_voff[j], soff, 0, 0);
-        } else {
-            load_k(pk0 + (size_t)t * tile_elems, KT, true);
-        }
-    };
-    auto fetch_v = [&](int t, int buf) {
-        if (PACKED) {
-            const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)(((size_t)kh * a.TPF + (t0 + t)) * C::T_BYTES));
-#pragma unroll
-            for (int j = 0; j < C::NI; ++j)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lds_void*)(vbuf0 + buf * VB_BYTES + (wave_u * C::NI + j) * 1024),
-                                                         16, v_voff[j], soff, 0, 0);
-        } else {
-            load_v(pv0 + (size_t)t * tile_elems, KT, true);
-        }
-    };
-    // make the fetched tiles visible to the workgroup
-    auto publish = [&]() {
-        if (PACKED) __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct loads have landed
-        __syncthreads();
-    };
-    // fragments of the fast path.  K: key block kb (32 keys), k-step ks.
-    auto k_frag_fast = [&](int buf, int kb, int ks) -> bf16x8 {
-        if (PACKED) return *reinterpret_cast<const bf16x8*>(kbuf0 + buf * KB_BYTES + kb * 32 * D * 2 + k_fragoff[ks]);
-        return *reinterpret_cast<const bf16x8*>(kbuf0 + buf * KB_BYTES + (kb * 32 + l32) * C::KROW + ks * 32 + half * 16);
-    };
-    // V^T: 16-key step t4, channel block db
-    auto v_frag_fast = [&](int buf, int t4, int db) -> bf16x8 {
-        if (PACKED) return *reinterpret_cast<const bf16x8*>(vbuf0 + buf * VB_BYTES + t4 * (D * 32) + db * 512 + v_fragoff);
-        return v_frag(vbuf0 + buf * VB_BYTES, t4, db);
-    };
-
-    if (F > 0) {
-        // prologue: K(0), V(0) and K(1) into LDS, scores of tile 0
-        fetch_k(0, 0);
-        fetch_v(0, 0);
-        load_q();
-        if (!PACKED) {
-            store_k(0);
-            store_v(0);
-        }
-        fetch_k(min(1, F - 1), 1);
-        if (!PACKED) store_k(1);
-        publish();
-        f32x16 sa[2], sb[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) sa[kb][v] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                sa[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag_fast(0, kb, ks), qf[ks], sa[kb], 0, 0, 0);
-        }
-        __syncthreads();   // K buffer 0 is refilled during the first step
-
-        // One pipelined step: probabilities and P V of tile i from s_cur while
-        // the scores of tile i+1 go to s_nxt; K(i+2) and V(i+1) are fetched.
-        //   slots  0- 7  S(i+1) first 32 keys   ||  row maximum of tile i
-        //   slots  8-15  S(i+1) second 32 keys  ||  exp of the first 32 keys
-        //   slots 16-23  P V first 32 keys      ||  exp of the second 32 keys
-        //   slots 24-31  P V second 32 keys     ||  staging of the fetched tiles
-        // `par` is i % 2 as a compile-time constant (buffer offsets become
-        // immediates), `nxt` says whether tile i+1 exists.
-        auto step = [&](auto par, auto nxt, int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2]) {
-            constexpr int P = decltype(par)::value;
-            constexpr bool has_next = decltype(nxt)::value;
-            // the buffers refilled here were last read in the previous step
-            fetch_k(min(i + 2, F - 1), P);
-            fetch_v(min(i + 1, F - 1), 1 - P);
-            auto kfrag = [&](int kb, int ks) { return k_frag_fast(1 - P, kb, ks); };
-            // P V slot j of block kb: 16-key step j / DB, channel block j % DB
-            auto vfrag = [&](int kb, int j) { return v_frag_fast(P, kb * 2 + j / DB, j % DB); };
-            bf16x8 f[3];
-            FDD_SCHED_FENCE();
-
-            // ---- slots 0-7 ----
-            float mx = -INFINITY;
-            if (has_next) {
-                f[0] = kfrag(0, 0);
-                f[1] = kfrag(0, 1);
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s_nxt[0][v] = 0.f;
-            }
-#pragma unroll
-            for (int j = 0; j < KS; ++j) {
-                if (has_next) {
-                    if (j + 2 < KS) f[(j + 2) % 3] = kfrag(0, j + 2);
-                    s_nxt[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[0], 0, 0, 0);
+                for (int jn = 0; jn < C::NI; ++jn) {
+                    const int r = ((tid_f >> 6) * C::NI + jn) * C::RPB + (tid_f & 63) / C::CH;
+                    const uint32_t col16 = (uint32_t)((((tid_f & 63) % C::CH) ^ ((((r / C::RPL) & 3) << 2) & (C::CH - 1))) * 16);
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(pv_rsrc, (lds_void*)(vdst + jn * 1024), 16,
+                                                             (uint32_t)r * stride2 + col16, soff, 0, 0);
                 }
-#pragma unroll
-                for (int v = j * (16 / KS); v < (j + 1) * (16 / KS); ++v) {
-                    mx = fmaxf(fmaxf(mx, s_cur[0][v]), s_cur[1][v]);
-                }
-                FDD_PIN(mx);
-                FDD_SCHED_FENCE();
             }
-            mx = fmaxf(mx, other_half(mx));
-            update_reference(mx);
-            const float mc = ((m_ref == -INFINITY) ? 0.f : m_ref) * a.c;
-            float acc = 0.f;
-            u32x4 pw[4];     // the B operands of P V as packed words
-            // four probabilities of block kb (registers 4e .. 4e+3), rounded into the B operands
-            auto exp_quad = [&](int kb, int e) {
-                float pr[4];
-#pragma unroll
-                for (int t = 0; t < 4; ++t) pr[t] = fast_exp2(fmaf(s_cur[kb][4 * e + t], a.c, -mc));
-                acc += (pr[0] + pr[1]) + (pr[2] + pr[3]);
-                typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-                bf16x2 lo = {(__bf16)pr[0], (__bf16)pr[1]}, hi = {(__bf16)pr[2], (__bf16)pr[3]};
-                uint32_t ulo = __builtin_bit_cast(uint32_t, lo), uhi = __builtin_bit_cast(uint32_t, hi);
-                FDD_PIN(ulo);
-                FDD_PIN(uhi);
-                FDD_PIN(acc);
-                pw[kb * 2 + e / 2][(e & 1) * 2] = ulo;
-                pw[kb * 2 + e / 2][(e & 1) * 2 + 1] = uhi;
-            };
-            FDD_SCHED_FENCE();
-
-            // ---- slots 8-15 ----
-            if (has_next) {
-                f[0] = kfrag(1, 0);
-                f[1] = kfrag(1, 1);
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s_nxt[1][v] = 0.f;
-            }
-#pragma unroll
-            for (int j = 0; j < KS; ++j) {
-                if (has_next) {
-                    if (j + 2 < KS) f[(j + 2) % 3] = kfrag(1, j + 2);
-                    s_nxt[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[1], 0, 0, 0);
-                }
-                if ((j * 4) % KS == 0) exp_quad(0, j * 4 / KS);
-                FDD_SCHED_FENCE();
-            }
-            p[0] = __builtin_bit_cast(bf16x8, pw[0]);
-            p[1] = __builtin_bit_cast(bf16x8, pw[1]);
-
-            // ---- slots 16-23 ----
-            constexpr int PVS = 2 * DB;      // P V MFMAs per 32-key block
-            f[0] = vfrag(0, 0);
-            f[1] = vfrag(0, 1);
-#pragma unroll
-            for (int j = 0; j < PVS; ++j) {
-                if (j + 2 < PVS) f[(j + 2) % 3] = vfrag(0, j + 2);
-                o[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], p[j / DB], o[j % DB], 0, 0, 0);
-                if ((j * 4) % PVS == 0) exp_quad(1, j * 4 / PVS);
-                FDD_SCHED_FENCE();
-            }
-            p[2] = __builtin_bit_cast(bf16x8, pw[2]);
-            p[3] = __builtin_bit_cast(bf16x8, pw[3]);
-            l_run += acc;
-
-            // ---- slots 24-31 ----
-            f[0] = vfrag(1, 0);
-            f[1] = vfrag(1, 1);
-#pragma unroll
-            for (int j = 0; j < PVS; ++j) {
-                if (j + 2 < PVS) f[(j + 2) % 3] = vfrag(1, j + 2);
-                o[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], p[2 + j / DB], o[j % DB], 0, 0, 0);
-                if (!PACKED) {
-                    if (j == 1) store_k(P);
-                    if (j == PVS / 2 + 1) store_v(1 - P);
-                }
-                FDD_SCHED_FENCE();
-            }
-            publish();
         };
-        using std::integral_constant;
-        const integral_constant<int, 0> even;
-        const integral_constant<int, 1> odd;
-        const integral_constant<bool, true> more;
-        const integral_constant<bool, false> last;
-        int i = 0;
-        for (; i + 2 < F; i += 2) {
-            step(even, more, i, sa, sb);
-            step(odd, more, i + 1, sb, sa);
-        }
-        if (i + 2 == F) {
-            step(even, more, i, sa, sb);
-            step(odd, last, i + 1, sb, sa);
-        } else {
-            step(even, last, i, sa, sb);
-        }
-    } else {
-        load_q();
-    }
-    f32x16 s[2];      // scores of a masked tile
+        // The first full tiles are requested before anything else is worked out,
+        // so that the rest of the set-up runs under their latency.
+        for (int j = 0; j < min(NB - 1, F); ++j) fetch_full(j);
+        issued = min(NB - 1, F);
+        FDD_SCHED_FENCE();
 
-    // ---- masked path: ragged last prefix tile and the in-block tail ------------
-    for (int i = F; i < n_tiles; ++i) {
-        const Tile t = tile_at(i);
-        load_k(t.k, t.valid, false);
-        load_v(t.v, t.valid, false);
-        store_rows(kreg, lds, C::KROW);
-        store_rows(vreg, lds + C::K_BYTES, C::VROW);
-        __syncthreads();
-        const bool wave_active = wave_has_rows &&
-            (t.rollout < 0 || (t.rollout >= wave_n_lo && t.rollout <= wave_n_hi));
-        if (wave_active) {
-            qk_block(lds, 0, s[0]);
-            qk_block(lds, 1, s[1]);
-            // register v of block kb is key kb*32 + (v/4)*8 + half*4 + v%4
-            const bool row_sees = (t.rollout < 0) || (t.rollout == my_rollout);
+        // ---- Q fragments: B operand of S^T = K Q^T ------------------------------
+        const int row0_wg = mt * MROWS;
+        const int row0 = row0_wg + wave * 32;
+        const int row = row0 + l32;
+        const bool row_ok = row < a.R;
+        const int nb = row_ok ? row / a.G : 0;           // n*B + b
+        const int g = row_ok ? row - nb * a.G : 0;
+        bf16x8 qf[KS];
+        {
+            const uint16_t* qp = a.q + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D + half * 8;
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                    const bool later = a.causal && t.rollout >= 0 && t.key0 + key > my_b;   // verify pass: causal inside the block
-                    if (!row_sees || key >= t.valid || later) s[kb][v] = -INFINITY;
-                }
-            update_reference(row_max(s[0], s[1]));
-            const float mc = ((m_ref == -INFINITY) ? 0.f : m_ref) * a.c;
-            exp_block(s[0], mc, p[0], p[1]);
-            exp_block(s[1], mc, p[2], p[3]);
-            pv_block(lds + C::K_BYTES, 0, p[0], p[1]);
-            pv_block(lds + C::K_BYTES, 1, p[2], p[3]);
-        }
-        __syncthreads();
-    }
-    const float m_run = m_ref;
-
-    // ---- epilogue of the segment ------------------------------------------------
-    const float l_tot = l_run + other_half(l_run);
-    if (row_ok) {
-        if (n_seg == 1) {
-            const float inv = 1.f / l_tot;
-            uint16_t* op = a.out + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const int d = db * 32 + v4 * 8 + half * 4;
-                    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-                    bf16x4 w;
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) w[j] = (__bf16)(o[db][v4 * 4 + j] * inv);
-                    *reinterpret_cast<bf16x4*>(op + d) = w;
-                }
-        } else {
-            const size_t prow = ((size_t)M * a.max_seg + seg) * MROWS + (wave * 32 + l32);
-            float* wo = a.ws_o + prow * D;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    const int d = db * 32 + v4 * 8 + half * 4;
-                    float4 w = make_float4(o[db][v4 * 4 + 0], o[db][v4 * 4 + 1], o[db][v4 * 4 + 2], o[db][v4 * 4 + 3]);
-                    *reinterpret_cast<float4*>(wo + d) = w;
-                }
-            if (half == 0) {
-                a.ws_ml[prow * 2 + 0] = m_run;
-                a.ws_ml[prow * 2 + 1] = l_tot;
+            for (int ks = 0; ks < KS; ++ks) {
+                u32x4 raw = {0u, 0u, 0u, 0u};
+                if (row_ok) raw = *reinterpret_cast<const u32x4*>(qp + ks * 16);
+                qf[ks] = __builtin_bit_cast(bf16x8, raw);
             }
         }
-    }
+        FDD_SCHED_FENCE();
+
+        // ---- the rest of the set-up ------------------------------------------------
+        int n_seg, seg;
+        if (a.S > 0) {
+            n_seg = a.S;
+            seg = piece;
+        } else {
+            const int first = wg_of_unit(M * a.TPU, a.base, a.rem);
+            n_seg = wg_of_unit((M + 1) * a.TPU - 1, a.base, a.rem) - first + 1;
+            seg = wg - first;
+        }
+        const int BG = a.B * a.G;
+        const int my_rollout = row_ok ? nb / a.B : -1;
+        const int my_b = row_ok ? nb - my_rollout * a.B : 0;   // position inside the block
+        // rollouts spanned by this wave's rows and by the whole M-tile
+        const int wave_n_lo = row0 / BG;
+        const int wave_n_hi = (min(row0 + 31, a.R - 1)) / BG;
+        const bool wave_has_rows = row0 < a.R;
+        const int wg_n_lo = __builtin_amdgcn_readfirstlane(row0_wg / BG);
+        const int wg_n_hi = __builtin_amdgcn_readfirstlane((min(row0_wg + MROWS - 1, a.R - 1)) / BG);
+        const int ttpr = (a.B + KT - 1) / KT;            // tail tiles per rollout
+        const int n_tail = (t_end == a.TPU) ? (wg_n_hi - wg_n_lo + 1) * ttpr : 0;
+        const int n_tiles = n_prefix + n_tail;
+
+        struct Tile {
+            int row_base;   // first key, as a row of prefix K/V or of block K/V
+            int valid;      // keys that exist
+            int rollout;    // whose rows may see it (-1: every row)
+            int key0;       // block position of the first key (tail tiles)
+        };
+        auto tile_at = [&](int j) -> Tile {
+            Tile t;
+            if (j < n_prefix) {
+                t.row_base = (t0 + j) * KT;
+                t.valid = min(KT, a.L - t.row_base);
+                t.rollout = -1;
+                t.key0 = 0;
+            } else {
+                const int jj = j - n_prefix;
+                int n = wg_n_lo + jj, k0 = 0;
+                if (ttpr > 1) {
+                    n = wg_n_lo + jj / ttpr;
+                    k0 = (jj % ttpr) * KT;
+                }
+                t.row_base = n * a.B + k0;
+                t.valid = min(KT, a.B - k0);
+                t.rollout = n;
+                t.key0 = k0;
+            }
+            return t;
+        };
+
+        // masked tile: rows beyond `valid` repeat the last valid row (finite values;
+        // their scores are masked), so nothing is read out of bounds
+        auto fetch_masked = [&](int j) {
+            const Tile t = tile_at(j);
+            const bool pre = j < n_prefix;
+            const uint32_t bytes = pre ? (uint32_t)a.L * stride2 : (uint32_t)(a.N * a.B) * stride2;
+            const __amdgpu_buffer_rsrc_t k_rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(pre ? a.pk : a.bk), 0, bytes, RSRC_FLAGS);
+            const __amdgpu_buffer_rsrc_t v_rsrc =
+                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(pre ? a.pv : a.bv), 0, bytes, RSRC_FLAGS);
+            const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)t.row_base * stride2 + (uint32_t)(kh * D * 2));
+            const uint32_t slot = (uint32_t)(j & (NB - 1)) * C::T_BYTES;
+            const int last = t.valid - 1;
+            int tid_f = tid;
+            FDD_PIN(tid_f);
+            const int wave_f = tid_f >> 6, lane_f = tid_f & 63;
+#pragma unroll
+            for (int jn = 0; jn < C::NI; ++jn) {
+                // this lane moves the 16 bytes that land at LDS piece (lane % CH) of row r of the tile
+                const int r = (wave_f * C::NI + jn) * C::RPB + lane_f / C::CH;
+                const uint32_t row_off = (uint32_t)min(r, last) * stride2;
+                const uint32_t k_col16 = (uint32_t)(((lane_f % C::CH) ^ ((r / C::RPL) & (C::CH - 1))) * 16);
+                const uint32_t v_col16 = (uint32_t)(((lane_f % C::CH) ^ ((((r / C::RPL) & 3) << 2) & (C::CH - 1))) * 16);
+                unsigned char* const kdst = lds + slot + (wave_u * C::NI + jn) * 1024;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(k_rsrc, (lds_void*)kdst, 16, row_off + k_col16, soff, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(v_rsrc, (lds_void*)(kdst + C::V_RING), 16, row_off + v_col16, soff, 0, 0);
+            }
+        };
+        // tile j: global memory -> ring slot j % NB, no registers in between
+        auto fetch = [&](int j_) {
+            const int j = __builtin_amdgcn_readfirstlane(j_);
+            if (j < F) fetch_full(j); else fetch_masked(j);
+            issued = j + 1;
+        };
+        // block until tile t has landed in LDS for the whole workgroup; tiles are
+        // fetched in order, IPT load instructions per wavefront each
+        int landed = -1;     // tiles up to this one are in LDS for every wavefront
+        auto wait_landed = [&](int t) {
+            landed = t;
+            const int k = issued - 1 - t;
+            if (k >= 3) wait_vm<3 * C::IPT>();
+            else if (k == 2) wait_vm<2 * C::IPT>();
+            else if (k == 1) wait_vm<C::IPT>();
+            else wait_vm<0>();
+            wg_barrier();
+        };
+
+        // masked tiles that fit the ring ahead of time
+        while (issued < min(NB - 1, n_tiles)) fetch(issued);
+
+        // ---- streaming-softmax state: one query row per lane --------------------
+        f32x16 o[DB];
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+        float m_ref = -INFINITY;   // reference value the exponentials are taken against (raw score units)
+        float l_run = 0.f;         // this lane's share of the running sum
+
+        // raise the reference when the tile maximum outgrew it by more than 2^8
+        auto update_reference = [&](float mx) {
+            // also true for the first tile (m_ref = -inf); never evaluates inf - inf
+            const bool need = (mx > m_ref) && ((mx - m_ref) * a.c > 8.f);
+            if (__any(need)) {
+                const float m_new = fmaxf(m_ref, mx);
+                const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+                const float alpha = fast_exp2((m_ref - m_use) * a.c);
+                l_run *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+                m_ref = m_new;
+            }
+        };
+
+        bf16x8 p[4];      // probabilities of a tile as MFMA B operands, one per 16-key step
+
+        // ---- full prefix tiles, software pipelined ---------------------------------
+        // (all of it: the Q loads sit between the tile requests in issue order)
+        wait_vm<0>();
+        wg_barrier();
+        landed = issued - 1;
+        if (F > 0) {
+            // prologue: scores of tile 0
+            f32x16 sa[2], sb[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sa[kb][v] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    sa[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(0, kb, ks), qf[ks], sa[kb], 0, 0, 0);
+            }
+
+            // One pipelined step: probabilities and P V of tile i from s_cur while
+            // the scores of tile i+1 go to s_nxt; tile i+3 is requested.
+            //   slots  0- 7  S(i+1) first 32 keys   ||  row maximum of tile i
+            //   slots  8-15  S(i+1) second 32 keys  ||  exp of the first 32 keys
+            //   slots 16-23  P V first 32 keys      ||  exp of the second 32 keys
+            //   slots 24-31  P V second 32 keys
+            // `nxt` says whether tile i+1 is a full tile too.  On entry tiles up to
+            // i+1 have landed; on exit tiles up to i+2 have.
+            auto step = [&](auto nxt, int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2]) {
+                constexpr bool has_next = decltype(nxt)::value;
+                // the slot refilled here held tile i-1, last read in the previous step
+                // (masked tiles are requested after the loop: their request code is long)
+                if (i + NB - 1 < F) {
+                    fetch_full(i + NB - 1);
+                    issued = i + NB;
+                }
+                // Per-lane fragment addresses of this step's slots.  They are made
+                // opaque so that the tile-relative parts stay in the 16-bit offset
+                // field of the LDS reads instead of being folded into new adds.
+                uint32_t ka[KS];
+                {
+                    uint32_t kaddr = (uint32_t)((i + 1) & (NB - 1)) * C::T_BYTES + k_fragoff0;
+                    FDD_PIN(kaddr);
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        ka[ks] = kaddr ^ (uint32_t)(ks << 5);
+                        FDD_PIN(ka[ks]);
+                    }
+                }
+                uint32_t vaddr = C::V_RING + (uint32_t)(i & (NB - 1)) * C::T_BYTES + (PACKED ? v_fragoff : vtr_off0);
+                FDD_PIN(vaddr);
+                auto kfrag = [&](int kb, int ks) {
+                    return *reinterpret_cast<const bf16x8*>(lds + ka[ks] + kb * 32 * D * 2);
+                };
+                // P V slot j of block kb: 16-key step j / DB, channel block j % DB
+                auto vfrag = [&](int kb, int j) -> bf16x8 {
+                    const int t4 = kb * 2 + j / DB, db = j % DB;
+                    if (PACKED) return *reinterpret_cast<const bf16x8*>(lds + vaddr + t4 * (D * 32) + db * 512);
+                    return v_frag_tr_at(vaddr, t4, db);
+                };
+                bf16x8 f[3];
+                FDD_SCHED_FENCE();
+
+                // ---- slots 0-7 ----
+                float mx = -INFINITY;
+                if (has_next) {
+                    f[0] = kfrag(0, 0);
+                    f[1] = kfrag(0, 1);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s_nxt[0][v] = 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    if (has_next) {
+                        if (j + 2 < KS) f[(j + 2) % 3] = kfrag(0, j + 2);
+                        s_nxt[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[0], 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int v = j * (16 / KS); v < (j + 1) * (16 / KS); ++v) {
+                        mx = fmaxf(fmaxf(mx, s_cur[0][v]), s_cur[1][v]);
+                    }
+                    FDD_PIN(mx);
+                    FDD_SCHED_FENCE();
+                }
+                mx = fmaxf(mx, other_half(mx));
+                update_reference(mx);
+                const float mc = ((m_ref == -INFINITY) ? 0.f : m_ref) * a.c;
+                float acc = 0.f;
+                u32x4 pw[4];     // the B operands of P V as packed words
+                // four probabilities of block kb (registers 4e .. 4e+3), rounded into the B operands
+                auto exp_quad = [&](int kb, int e) {
+                    float pr[4];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) pr[t] = fast_exp2(fmaf(s_cur[kb][4 * e + t], a.c, -mc));
+                    acc += (pr[0] + pr[1]) + (pr[2] + pr[3]);
+                    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+                    bf16x2 lo = {(__bf16)pr[0], (__bf16)pr[1]}, hi = {(__bf16)pr[2], (__bf16)pr[3]};
+                    uint32_t ulo = __builtin_bit_cast(uint32_t, lo), uhi = __builtin_bit_cast(uint32_t, hi);
+                    FDD_PIN(ulo);
+                    FDD_PIN(uhi);
+                    FDD_PIN(acc);
+                    pw[kb * 2 + e / 2][(e & 1) * 2] = ulo;
+                    pw[kb * 2 + e / 2][(e & 1) * 2 + 1] = uhi;
+                };
+                FDD_SCHED_FENCE();
+
+                // ---- slots 8-15 ----
+                if (has_next) {
+                    f[0] = kfrag(1, 0);
+                    f[1] = kfrag(1, 1);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s_nxt[1][v] = 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < KS; ++j) {
+                    if (has_next) {
+                        if (j + 2 < KS) f[(j + 2) % 3] = kfrag(1, j + 2);
+                        s_nxt[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[1], 0, 0, 0);
+                    }
+                    if ((j * 4) % KS == 0) exp_quad(0, j * 4 / KS);
+                    FDD_SCHED_FENCE();
+                }
+                p[0] = __builtin_bit_cast(bf16x8, pw[0]);
+                p[1] = __builtin_bit_cast(bf16x8, pw[1]);
+
+                // ---- slots 16-23 ----
+                constexpr int PVS = 2 * DB;      // P V MFMAs per 32-key block
+                f[0] = vfrag(0, 0);
+                f[1] = vfrag(0, 1);
+#pragma unroll
+                for (int j = 0; j < PVS; ++j) {
+                    if (j + 2 < PVS) f[(j + 2) % 3] = vfrag(0, j + 2);
+                    o[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], p[j / DB], o[j % DB], 0, 0, 0);
+                    if ((j * 4) % PVS == 0) exp_quad(1, j * 4 / PVS);
+                    FDD_SCHED_FENCE();
+                }
+                p[2] = __builtin_bit_cast(bf16x8, pw[2]);
+                p[3] = __builtin_bit_cast(bf16x8, pw[3]);
+                l_run += acc;
+
+                // ---- slots 24-31 ----
+                f[0] = vfrag(1, 0);
+                f[1] = vfrag(1, 1);
+#pragma unroll
+                for (int j = 0; j < PVS; ++j) {
+                    if (j + 2 < PVS) f[(j + 2) % 3] = vfrag(1, j + 2);
+                    o[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], p[2 + j / DB], o[j % DB], 0, 0, 0);
+                    FDD_SCHED_FENCE();
+                }
+                // tile i+2 must have landed; the one requested above may still be on its way
+                if (i + 3 < F) wait_vm<C::IPT>(); else wait_vm<0>();
+                wg_barrier();
+            };
+            const std::integral_constant<bool, true> more;
+            const std::integral_constant<bool, false> last;
+            int i = 0;
+            for (; i + 2 < F; i += 2) {
+                step(more, i, sa, sb);
+                step(more, i + 1, sb, sa);
+            }
+            if (i + 2 == F) {
+                step(more, i, sa, sb);
+                step(last, i + 1, sb, sa);
+            } else {
+                step(last, i, sa, sb);
+            }
+            landed = issued - 1;     // the last step waits for everything requested
+        }
+
+        // ---- masked tiles: ragged last prefix tile and the in-block tail ------------
+        // On entry to iteration j tile j has landed.
+        for (int j = F; j < n_tiles; ++j) {
+            // the slots refilled here held tiles up to j-1, last read before the previous barrier
+            while (issued < min(n_tiles, j + NB)) fetch(issued);
+            if (landed < j) wait_landed(j);
+            const Tile t = tile_at(j);
+            const uint32_t kbase = (uint32_t)(j & (NB - 1)) * C::T_BYTES;
+            const uint32_t vbase = C::V_RING + kbase;
+            const bool wave_active = wave_has_rows &&
+                (t.rollout < 0 || (t.rollout >= wave_n_lo && t.rollout <= wave_n_hi));
+            if (wave_active) {
+                f32x16 s[2];
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks)
+                        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(kbase, kb, ks), qf[ks], s[kb], 0, 0, 0);
+                }
+                // register v of block kb is key kb*32 + (v/4)*8 + half*4 + v%4
+                const bool row_sees = (t.rollout < 0) || (t.rollout == my_rollout);
+                float mx = -INFINITY;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                        const bool later = a.causal && t.rollout >= 0 && t.key0 + key > my_b;   // verify pass: causal inside the block
+                        if (!row_sees || key >= t.valid || later) s[kb][v] = -INFINITY;
+                        mx = fmaxf(mx, s[kb][v]);
+                    }
+                update_reference(fmaxf(mx, other_half(mx)));
+                const float mc = ((m_ref == -INFINITY) ? 0.f : m_ref) * a.c;
+                float acc = 0.f;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float pr = fast_exp2(fmaf(s[kb][v], a.c, -mc));
+                        acc += pr;
+                        p[kb * 2 + v / 8][v % 8] = (__bf16)pr;
+                    }
+                l_run += acc;
+#pragma unroll
+                for (int t4 = 0; t4 < 4; ++t4)
+#pragma unroll
+                    for (int db = 0; db < DB; ++db)
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag_tr_at(vbase + vtr_off0, t4, db), p[t4], o[db], 0, 0, 0);
+            }
+            if (j + 1 < n_tiles) wait_landed(j + 1); else wg_barrier();
+        }
+        const float m_run = m_ref;
+
+        // ---- epilogue of the segment ------------------------------------------------
+        const float l_tot = l_run + other_half(l_run);
+        if (row_ok) {
+            if (n_seg == 1) {
+                const float inv = 1.f / l_tot;
+                uint16_t* op = a.out + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        const int d = db * 32 + v4 * 8 + half * 4;
+                        typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+                        bf16x4 w;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) w[j] = (__bf16)(o[db][v4 * 4 + j] * inv);
+                        *reinterpret_cast<bf16x4*>(op + d) = w;
+                    }
+            } else {
+                const size_t prow = ((size_t)M * a.max_seg + seg) * MROWS + (wave * 32 + l32);
+                float* wo = a.ws_o + prow * D;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        const int d = db * 32 + v4 * 8 + half * 4;
+                        float4 w = make_float4(o[db][v4 * 4 + 0], o[db][v4 * 4 + 1], o[db][v4 * 4 + 2], o[db][v4 * 4 + 3]);
+                        *reinterpret_cast<float4*>(wo + d) = w;
+                    }
+                if (half == 0) {
+                    a.ws_ml[prow * 2 + 0] = m_run;
+                    a.ws_ml[prow * 2 + 1] = l_tot;
+                }
+            }
+        }
     }   // next segment of this workgroup's range
 #endif
 }
@@ -680,10 +707,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
 // per (tile, KV head): stage the tile [key][d] in LDS, then let the LDS
 // transpose read do the transposition; a wavefront stores two 512-byte runs.
 template <int D>
+struct PackCfg {
+    static constexpr int THREADS = 512;
+    static constexpr int VROW = D * 2 + 64;              // padded row: conflict-free transposing reads
+    static constexpr int V_BYTES = KT * VROW;
+    static constexpr int K_PER_THREAD = KT * (D / 8) / THREADS;
+    static constexpr int T_BYTES = KT * D * 2;
+};
+
+template <int D>
 __global__ __launch_bounds__(512) void vt_pack_kernel(const uint16_t* __restrict__ pv, uint16_t* __restrict__ vt,
                                                        int Hkv, int TPF)
 {
-    using C = Cfg<D, 8>;
+    using C = PackCfg<D>;
     constexpr int DB = D / 32;
     __shared__ __align__(16) unsigned char tile[C::V_BYTES];
     const int t = blockIdx.x, kh = blockIdx.y;
@@ -716,8 +752,7 @@ template <int D, int WAVES, bool PACKED>
 hipError_t launch(const Args& a, bool pack_now, hipStream_t stream, hipEvent_t before_main)
 {
     using C = Cfg<D, WAVES>;
-    const size_t lds_bytes = PACKED ? 4 * (size_t)C::T_BYTES : 2 * (size_t)C::BUF_BYTES;
-    static_assert(4 * C::T_BYTES >= C::BUF_BYTES, "the masked path stages one padded K and V tile");
+    const size_t lds_bytes = C::LDS_BYTES;
     const auto kern = &attn_bf16_kernel<D, WAVES, PACKED>;
     static bool attr_done = false;   // per instantiation
     if (!attr_done) {
@@ -736,7 +771,7 @@ hipError_t launch(const Args& a, bool pack_now, hipStream_t stream, hipEvent_t b
         hipError_t e = hipEventRecord(before_main, stream);
         if (e != hipSuccess) return e;
     }
-    const int grid = (a.W + kNumXCD - 1) / kNumXCD * kNumXCD;   // padded so that every XCD gets the same count
+    const int grid = a.per_xcd * kNumXCD;   // padded so that every XCD gets the same count
     hipLaunchKernelGGL(kern, dim3(grid), dim3(C::THREADS), lds_bytes, stream, a);
     return hipGetLastError();
 }
@@ -762,7 +797,9 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
                     : static_cast<const uint16_t*>(p.prefix_v_packed);
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.TPF = p.L / 64;
-    a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.U = plan.U; a.S = plan.uniform;
+    a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.S = plan.uniform;
+    a.per_xcd = (plan.W + kNumXCD - 1) / kNumXCD;
+    a.base = (int)(plan.U / plan.W); a.rem = (int)(plan.U % plan.W);
     a.causal = (p.flags & FDD_ATTN_CAUSAL_BLOCK) ? 1 : 0;
     a.c = scale * 1.4426950408889634f;
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;

@@ -188,51 +188,102 @@ struct CombineArgs {
     const float* ws_o;
     const float* ws_ml;
     void* out;
-    int B, Hq, Hkv, G, R, MT, mrows, D, bf16;
+    int Hq, G, R, MT, mrows, D, bf16;
     int max_seg;     // slots per M-tile in the workspace
     int fixed_seg;   // > 0: every M-tile has this many segments; 0: stream-K ranges
-    int TPU, W;
-    long long U;
+    int TPU, base, rem;
+    int SG;          // segment groups: the segments of a row are shared out over SG threads per channel quad
+    int RB;          // rows per block; RB * SG * D/4 = 256 threads
     float c;
 };
 
+// grid (Hkv*MT, ceil(mrows / RB)).  Thread (r, sg, d4) sums segments sg, sg+SG, ..
+// of row r for 4 channels, four loads in flight at a time; the SG partial sums
+// are then added in the order sg = 0, 1, .. by the thread with sg = 0.
 __global__ __launch_bounds__(256) void attn_combine_kernel(CombineArgs a)
 {
+    extern __shared__ __align__(16) float smem[];
     const int d4n = a.D / 4;
-    const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    const long long total = (long long)a.Hkv * a.R * d4n;
-    if (idx >= total) return;
-    const int d4 = (int)(idx % d4n);
-    const long long hr = idx / d4n;
-    const int row = (int)(hr % a.R);
-    const int kh = (int)(hr / a.R);
-    const int mt = row / a.mrows, rit = row % a.mrows;
-    const long long M = (long long)kh * a.MT + mt;
+    const int tid = (int)threadIdx.x;
+    const int d4 = tid % d4n, sg = (tid / d4n) % a.SG, r = tid / (d4n * a.SG);
+    const int M = (int)blockIdx.x;
+    const int kh = M / a.MT, mt = M - kh * a.MT;
+    const int rit0 = (int)blockIdx.y * a.RB;
     int n_seg = a.fixed_seg;
     if (n_seg == 0) {
         // same arithmetic as the attention kernel: workgroups whose unit range meets this M-tile
-        const int first = (int)(((M * a.TPU + 1) * a.W + a.U - 1) / a.U) - 1;
-        const int last = (int)(((M + 1) * a.TPU * a.W + a.U - 1) / a.U) - 1;
-        n_seg = last - first + 1;
-        if (n_seg == 1) return;     // written in final form by its only segment
+        n_seg = wg_of_unit((M + 1) * a.TPU - 1, a.base, a.rem) - wg_of_unit(M * a.TPU, a.base, a.rem) + 1;
     }
-    const size_t p0 = ((size_t)M * a.max_seg) * a.mrows + rit;
+    if (n_seg == 1) return;     // written in final form by its only segment
+    float* const sm = smem;                           // [RB][n_seg] segment maxima
+    float* const sl = smem + a.RB * n_seg;            // [RB][n_seg] segment sums
+    float4* const red = reinterpret_cast<float4*>(smem + ((2 * a.RB * a.max_seg + 3) & ~3));   // [RB][SG][d4n]
+    float* const redl = reinterpret_cast<float*>(red + a.RB * a.SG * d4n);        // [RB][SG]
+    const size_t p0 = ((size_t)M * a.max_seg) * a.mrows + rit0;
+    for (int i = tid; i < a.RB * n_seg; i += 256) {
+        const int rr = i / n_seg, s = i - rr * n_seg;
+        float m = -INFINITY, l = 0.f;
+        if (rit0 + rr < a.mrows) {
+            const float2 ml = *reinterpret_cast<const float2*>(a.ws_ml + (p0 + rr + (size_t)s * a.mrows) * 2);
+            m = ml.x;
+            l = ml.y;
+        }
+        sm[i] = m;
+        sl[i] = l;
+    }
+    __syncthreads();
+    const int rit = rit0 + r;
+    const int row = mt * a.mrows + rit;
+    const bool live = rit < a.mrows && row < a.R;
     float mstar = -INFINITY;
-    for (int s = 0; s < n_seg; ++s) mstar = fmaxf(mstar, a.ws_ml[(p0 + (size_t)s * a.mrows) * 2]);
+    for (int s = 0; s < n_seg; ++s) mstar = fmaxf(mstar, sm[r * n_seg + s]);
     float l = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < n_seg; ++s) {
-        const size_t pr = p0 + (size_t)s * a.mrows;
-        const float w = exp2f((a.ws_ml[pr * 2] - mstar) * a.c);
-        l = fmaf(a.ws_ml[pr * 2 + 1], w, l);
-        const float4 x = *reinterpret_cast<const float4*>(a.ws_o + pr * a.D + d4 * 4);
-        acc.x = fmaf(x.x, w, acc.x);
-        acc.y = fmaf(x.y, w, acc.y);
-        acc.z = fmaf(x.z, w, acc.z);
-        acc.w = fmaf(x.w, w, acc.w);
+    if (live) {
+        const float* src = a.ws_o + (p0 + r) * a.D + d4 * 4;
+        const size_t seg_stride = (size_t)a.mrows * a.D;
+        for (int s0 = sg; s0 < n_seg; s0 += 4 * a.SG) {
+            float4 x[4];
+            float w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + u * a.SG;
+                x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+                w[u] = 0.f;
+                if (s < n_seg) {
+                    x[u] = *reinterpret_cast<const float4*>(src + (size_t)s * seg_stride);
+                    w[u] = exp2f((sm[r * n_seg + s] - mstar) * a.c);
+                    l = fmaf(sl[r * n_seg + s], w[u], l);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                acc.x = fmaf(x[u].x, w[u], acc.x);
+                acc.y = fmaf(x[u].y, w[u], acc.y);
+                acc.z = fmaf(x[u].z, w[u], acc.z);
+                acc.w = fmaf(x[u].w, w[u], acc.w);
+            }
+        }
     }
+    if (a.SG > 1) {
+        red[(r * a.SG + sg) * d4n + d4] = acc;
+        if (d4 == 0) redl[r * a.SG + sg] = l;
+        __syncthreads();
+        if (sg != 0) return;
+        acc = red[(r * a.SG) * d4n + d4];
+        l = redl[r * a.SG];
+        for (int k = 1; k < a.SG; ++k) {
+            const float4 y = red[(r * a.SG + k) * d4n + d4];
+            acc.x += y.x;
+            acc.y += y.y;
+            acc.z += y.z;
+            acc.w += y.w;
+            l += redl[r * a.SG + k];
+        }
+    }
+    if (!live) return;
     const float inv = 1.f / l;
-    const int nb = row / a.G, g = row % a.G;
+    const int nb = row / a.G, g = row - nb * a.G;
     const size_t off = ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * a.D + d4 * 4;
     if (a.bf16) {
         typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
@@ -278,14 +329,26 @@ hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, f
     a.ws_o = static_cast<const float*>(p.workspace);
     a.ws_ml = reinterpret_cast<const float*>(static_cast<const char*>(p.workspace) + plan.ws_o_bytes);
     a.out = p.out;
-    a.B = p.B; a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = plan.G; a.R = plan.R; a.MT = plan.MT;
+    a.Hq = p.Hq; a.G = plan.G; a.R = plan.R; a.MT = plan.MT;
     a.mrows = plan.mtile_rows; a.D = p.D; a.bf16 = (p.dtype == FDD_BF16);
-    a.max_seg = plan.max_seg; a.fixed_seg = a.bf16 ? 0 : plan.splits;
-    a.TPU = plan.TPU; a.W = plan.W; a.U = plan.U;
+    a.max_seg = plan.max_seg;
+    a.fixed_seg = a.bf16 ? plan.uniform : plan.splits;
+    a.TPU = plan.TPU;
+    a.base = a.bf16 ? (int)(plan.U / plan.W) : 1;
+    a.rem = a.bf16 ? (int)(plan.U % plan.W) : 0;
     a.c = scale * 1.4426950408889634f;
-    const long long total = (long long)p.Hkv * plan.R * (p.D / 4);
-    const int grid = (int)((total + 255) / 256);
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(grid), dim3(256), 0, s, a);
+    // more threads per row when the rows are few and the segments many
+    const long long rows = (long long)p.Hkv * plan.R;
+    const int seg_hint = a.fixed_seg > 0 ? a.fixed_seg : plan.max_seg;
+    int sg = 1;
+    while (sg < 8 && sg * 2 <= seg_hint && rows * sg < 16384) sg *= 2;
+    a.SG = sg;
+    a.RB = 256 / (sg * (p.D / 4));
+    const size_t smem = (size_t)((2 * a.RB * plan.max_seg + 3) & ~3) * sizeof(float) + (size_t)a.RB * sg * (p.D / 4) * sizeof(float4) +
+                        (size_t)a.RB * sg * sizeof(float);
+    if (smem > 60 * 1024) return hipErrorInvalidValue;
+    const dim3 grid(p.Hkv * plan.MT, (plan.mtile_rows + a.RB - 1) / a.RB);
+    hipLaunchKernelGGL(attn_combine_kernel, grid, dim3(256), smem, s, a);
     return hipGetLastError();
 }
 

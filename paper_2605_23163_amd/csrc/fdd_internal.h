@@ -23,9 +23,11 @@ constexpr int kNumXCD = 8;
 // leaves a partial (m, l, o[D]) in slot M*max_seg + seg of the workspace
 // unless it is the M-tile's only segment.
 //   fp32 path : `splits` equal pieces per M-tile, one workgroup each.
-//   bf16 path : stream-K.  The unit is one key tile of one M-tile (TPU units
-//               per M-tile, U in total); workgroup w of W owns units
-//               [U w / W, U (w+1) / W).
+//   bf16 path : the unit is one key tile of one M-tile (TPU units per M-tile,
+//               U in total).  Either every M-tile is cut into `uniform` equal
+//               pieces, piece s covering tiles [TPU s / S, TPU (s+1) / S), or
+//               (stream-K) workgroup w of W owns the contiguous unit range
+//               [unit_begin(w), unit_begin(w+1)), which may cross M-tiles.
 struct AttnPlan {
     int G;            // query heads per KV head
     int R;            // stacked rows per KV head
@@ -46,6 +48,15 @@ struct AttnPlan {
 };
 
 bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan);
+
+// Stream-K ranges: U units over W workgroups, base = U / W, rem = U % W; the
+// first `rem` workgroups own base + 1 units, the others base (>= 1).
+__host__ __device__ inline int unit_begin(int w, int base, int rem) { return w * base + (w < rem ? w : rem); }
+__host__ __device__ inline int wg_of_unit(int u, int base, int rem)
+{
+    const int cut = rem * (base + 1);
+    return u < cut ? u / (base + 1) : rem + (u - cut) / base;
+}
 
 // `before_main`, if not null, is recorded on the stream right before the main kernel (after the V pre-pass).
 hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s, hipEvent_t before_main);
