@@ -194,7 +194,13 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     // K fragment of k-step ks: row l32 of a 32-key block, 16-byte piece (2 ks + half)
     // at its swizzled place, which is the place of k-step 0 with ks XORed in
     const uint32_t k_fragoff0 = (uint32_t)(l32 * D * 2 + ((((l32 / C::RPL) & (C::CH - 1)) ^ half) << 4));
-    const uint32_t v_fragoff = (uint32_t)(half * (D * 16) + l32 * 16);   // packed V^T: [16-key step][half][d][8 keys]
+    uint32_t k_fragoff[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) k_fragoff[ks] = k_fragoff0 ^ (uint32_t)(ks << 5);
+    // packed V^T: [16-key step][half][d][8 keys]; the ring's offset is part of the register
+    // because the offset field of an LDS read ends at 64 KB
+    uint32_t v_fragoff_ring = (uint32_t)(C::V_RING + half * (D * 16) + l32 * 16);
+    FDD_PIN(v_fragoff_ring);
     // Unpacked V, transposing reads.  In a 16-lane group, lane 4j+q points at 4
     // channels of key row j; the read returns to lane i the 4 keys of channel i.
     // Element e of the assembled fragment is key 16 t4 + 8 (e/4) + 4 half + e%4,
@@ -207,6 +213,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const int sw = (((row_l / C::RPL) & 3) << 2) & (C::CH - 1);
         vtr_off0 = (uint32_t)(row_l * D * 2 + ((x ^ sw) << 4) + (lane & 1) * 8);
     }
+    uint32_t vtr_off_ring = C::V_RING + vtr_off0;
+    FDD_PIN(vtr_off_ring);
     // Tile movement: piece jn of this wavefront covers rows (wave NI + jn) RPB .. of
     // a tile; this lane moves the 16 bytes that land at LDS piece (lane % CH) of
     // its row.  K: the pieces of a row are XOR-swizzled by the row's bank line.
@@ -227,7 +235,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.vt), 0, (uint32_t)(a.Hkv * a.TPF) * C::T_BYTES, RSRC_FLAGS);
 
     auto k_frag = [&](uint32_t kbase, int kb, int ks) -> bf16x8 {
-        return *reinterpret_cast<const bf16x8*>(lds + ((kbase + k_fragoff0) ^ (uint32_t)(ks << 5)) + kb * 32 * D * 2);
+        return *reinterpret_cast<const bf16x8*>(lds + (kbase + k_fragoff[ks]) + kb * 32 * D * 2);
     };
     // `vaddr` = slot base + vtr_off0
     auto v_frag_tr_at = [&](uint32_t vaddr, int t4, int db) -> bf16x8 {
@@ -263,8 +271,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         // ---- tile j: global memory -> ring slot j % NB, no registers in between ----
         int issued = 0;
         // full prefix tile (j < F): offsets were prepared once, only the scalar tile offset changes
-        auto fetch_full = [&](int j) {
-            const uint32_t slot = (uint32_t)(j & (NB - 1)) * C::T_BYTES;
+        auto fetch_full = [&](int j, uint32_t slot) {     // slot = (j % NB) * T_BYTES, a constant where it matters
             const uint32_t soff = (uint32_t)((t0 + j) * KT) * stride2 + (uint32_t)(kh * D * 2);
             unsigned char* const kdst = lds + slot + wave_u * (C::NI * 1024);
             unsigned char* const vdst = kdst + C::V_RING;
@@ -288,7 +295,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         };
         // The first full tiles are requested before anything else is worked out,
         // so that the rest of the set-up runs under their latency.
-        for (int j = 0; j < min(NB - 1, F); ++j) fetch_full(j);
+        for (int j = 0; j < min(NB - 1, F); ++j) fetch_full(j, (uint32_t)j * C::T_BYTES);
         issued = min(NB - 1, F);
         FDD_SCHED_FENCE();
 
@@ -393,7 +400,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         // tile j: global memory -> ring slot j % NB, no registers in between
         auto fetch = [&](int j_) {
             const int j = __builtin_amdgcn_readfirstlane(j_);
-            if (j < F) fetch_full(j); else fetch_masked(j);
+            if (j < F) fetch_full(j, (uint32_t)(j & (NB - 1)) * C::T_BYTES); else fetch_masked(j);
             issued = j + 1;
         };
         // block until tile t has landed in LDS for the whole workgroup; tiles are
@@ -463,57 +470,43 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             //   slots  8-15  S(i+1) second 32 keys  ||  exp of the first 32 keys
             //   slots 16-23  P V first 32 keys      ||  exp of the second 32 keys
             //   slots 24-31  P V second 32 keys
-            // `nxt` says whether tile i+1 is a full tile too.  On entry tiles up to
-            // i+1 have landed; on exit tiles up to i+2 have.
-            auto step = [&](auto nxt, int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2]) {
-                constexpr bool has_next = decltype(nxt)::value;
+            // `par` is i % NB as a compile-time constant: ring slots become
+            // immediate offsets of the LDS reads.  The scores of tile i+1 are
+            // computed whether or not it is a full tile (from whatever its slot
+            // holds); they are only used if it is.  On entry tiles up to i+1 have
+            // landed; on exit tiles up to i+2 have.
+            auto step = [&](auto par, int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2]) {
+                constexpr int P = decltype(par)::value;
+                constexpr uint32_t KSLOT = (uint32_t)((P + 1) % NB) * C::T_BYTES;
+                constexpr uint32_t VSLOT = (uint32_t)P * C::T_BYTES;
                 // the slot refilled here held tile i-1, last read in the previous step
                 // (masked tiles are requested after the loop: their request code is long)
                 if (i + NB - 1 < F) {
-                    fetch_full(i + NB - 1);
+                    fetch_full(i + NB - 1, (uint32_t)((P + NB - 1) % NB) * C::T_BYTES);
                     issued = i + NB;
                 }
-                // Per-lane fragment addresses of this step's slots.  They are made
-                // opaque so that the tile-relative parts stay in the 16-bit offset
-                // field of the LDS reads instead of being folded into new adds.
-                uint32_t ka[KS];
-                {
-                    uint32_t kaddr = (uint32_t)((i + 1) & (NB - 1)) * C::T_BYTES + k_fragoff0;
-                    FDD_PIN(kaddr);
-#pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) {
-                        ka[ks] = kaddr ^ (uint32_t)(ks << 5);
-                        FDD_PIN(ka[ks]);
-                    }
-                }
-                uint32_t vaddr = C::V_RING + (uint32_t)(i & (NB - 1)) * C::T_BYTES + (PACKED ? v_fragoff : vtr_off0);
-                FDD_PIN(vaddr);
                 auto kfrag = [&](int kb, int ks) {
-                    return *reinterpret_cast<const bf16x8*>(lds + ka[ks] + kb * 32 * D * 2);
+                    return *reinterpret_cast<const bf16x8*>(lds + k_fragoff[ks] + (KSLOT + kb * 32 * D * 2));
                 };
                 // P V slot j of block kb: 16-key step j / DB, channel block j % DB
                 auto vfrag = [&](int kb, int j) -> bf16x8 {
                     const int t4 = kb * 2 + j / DB, db = j % DB;
-                    if (PACKED) return *reinterpret_cast<const bf16x8*>(lds + vaddr + t4 * (D * 32) + db * 512);
-                    return v_frag_tr_at(vaddr, t4, db);
+                    if (PACKED) return *reinterpret_cast<const bf16x8*>(lds + v_fragoff_ring + (VSLOT + t4 * (D * 32) + db * 512));
+                    return v_frag_tr_at(vtr_off_ring + VSLOT, t4, db);
                 };
                 bf16x8 f[3];
                 FDD_SCHED_FENCE();
 
                 // ---- slots 0-7 ----
                 float mx = -INFINITY;
-                if (has_next) {
-                    f[0] = kfrag(0, 0);
-                    f[1] = kfrag(0, 1);
+                f[0] = kfrag(0, 0);
+                f[1] = kfrag(0, 1);
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) s_nxt[0][v] = 0.f;
-                }
+                for (int v = 0; v < 16; ++v) s_nxt[0][v] = 0.f;
 #pragma unroll
                 for (int j = 0; j < KS; ++j) {
-                    if (has_next) {
-                        if (j + 2 < KS) f[(j + 2) % 3] = kfrag(0, j + 2);
-                        s_nxt[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[0], 0, 0, 0);
-                    }
+                    if (j + 2 < KS) f[(j + 2) % 3] = kfrag(0, j + 2);
+                    s_nxt[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[0], 0, 0, 0);
 #pragma unroll
                     for (int v = j * (16 / KS); v < (j + 1) * (16 / KS); ++v) {
                         mx = fmaxf(fmaxf(mx, s_cur[0][v]), s_cur[1][v]);
@@ -544,18 +537,14 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                 FDD_SCHED_FENCE();
 
                 // ---- slots 8-15 ----
-                if (has_next) {
-                    f[0] = kfrag(1, 0);
-                    f[1] = kfrag(1, 1);
+                f[0] = kfrag(1, 0);
+                f[1] = kfrag(1, 1);
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) s_nxt[1][v] = 0.f;
-                }
+                for (int v = 0; v < 16; ++v) s_nxt[1][v] = 0.f;
 #pragma unroll
                 for (int j = 0; j < KS; ++j) {
-                    if (has_next) {
-                        if (j + 2 < KS) f[(j + 2) % 3] = kfrag(1, j + 2);
-                        s_nxt[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[1], 0, 0, 0);
-                    }
+                    if (j + 2 < KS) f[(j + 2) % 3] = kfrag(1, j + 2);
+                    s_nxt[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], qf[j], s_nxt[1], 0, 0, 0);
                     if ((j * 4) % KS == 0) exp_quad(0, j * 4 / KS);
                     FDD_SCHED_FENCE();
                 }
@@ -590,18 +579,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                 if (i + 3 < F) wait_vm<C::IPT>(); else wait_vm<0>();
                 wg_barrier();
             };
-            const std::integral_constant<bool, true> more;
-            const std::integral_constant<bool, false> last;
-            int i = 0;
-            for (; i + 2 < F; i += 2) {
-                step(more, i, sa, sb);
-                step(more, i + 1, sb, sa);
-            }
-            if (i + 2 == F) {
-                step(more, i, sa, sb);
-                step(last, i + 1, sb, sa);
-            } else {
-                step(last, i, sa, sb);
+            const std::integral_constant<int, 0> r0;
+            const std::integral_constant<int, 1> r1;
+            const std::integral_constant<int, 2> r2;
+            const std::integral_constant<int, 3> r3;
+            for (int i = 0;;) {
+                step(r0, i, sa, sb);
+                if (++i == F) break;
+                step(r1, i, sb, sa);
+                if (++i == F) break;
+                step(r2, i, sa, sb);
+                if (++i == F) break;
+                step(r3, i, sb, sa);
+                if (++i == F) break;
             }
             landed = issued - 1;     // the last step waits for everything requested
         }
@@ -614,7 +604,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             if (landed < j) wait_landed(j);
             const Tile t = tile_at(j);
             const uint32_t kbase = (uint32_t)(j & (NB - 1)) * C::T_BYTES;
-            const uint32_t vbase = C::V_RING + kbase;
             const bool wave_active = wave_has_rows &&
                 (t.rollout < 0 || (t.rollout >= wave_n_lo && t.rollout <= wave_n_hi));
             if (wave_active) {
@@ -655,7 +644,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                 for (int t4 = 0; t4 < 4; ++t4)
 #pragma unroll
                     for (int db = 0; db < DB; ++db)
-                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag_tr_at(vbase + vtr_off0, t4, db), p[t4], o[db], 0, 0, 0);
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag_tr_at(vtr_off_ring + kbase, t4, db), p[t4], o[db], 0, 0, 0);
             }
             if (j + 1 < n_tiles) wait_landed(j + 1); else wg_barrier();
         }
