@@ -25,7 +25,7 @@ def build(force: bool = False) -> str:
     """Compile the C oracle (gcc -O2 -fopenmp)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + f".{os.getpid()}.tmp"
-        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-ffp-contract=off",
                                "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
@@ -43,6 +43,16 @@ def _load():
         lib.fddo_block_attn_ex.argtypes = [c.c_int] * 7 + [c.c_double, c.c_int] + [c.c_void_p] * 6 + [c.c_int64, c.c_void_p]
         lib.fddo_verify_step.restype = c.c_int
         lib.fddo_verify_step.argtypes = [c.c_int, c.c_int, c.c_int64, c.c_int] + [c.c_void_p] * 8
+        lib.fddo_verify_step_ex.restype = c.c_int
+        lib.fddo_verify_step_ex.argtypes = [c.c_int, c.c_int, c.c_int64, c.c_int] + [c.c_void_p] * 8 + [c.c_float, c.c_uint64]
+        lib.fddo_philox4x32_10.restype = None
+        lib.fddo_philox4x32_10.argtypes = [c.c_void_p] * 3
+        lib.fddo_flog2.restype = c.c_float
+        lib.fddo_flog2.argtypes = [c.c_float]
+        lib.fddo_sample_key.restype = c.c_float
+        lib.fddo_sample_key.argtypes = [c.c_float, c.c_float, c.c_uint64, c.c_uint32, c.c_int64]
+        lib.fddo_sample_scale.restype = c.c_float
+        lib.fddo_sample_scale.argtypes = [c.c_float]
         lib.fddo_unmask_step.restype = c.c_int
         lib.fddo_unmask_step.argtypes = [c.c_int, c.c_int, c.c_int64, c.c_int, c.c_double] + [c.c_void_p] * 8
         lib.fddo_block_kv_update.restype = c.c_int
@@ -123,8 +133,10 @@ def unmask_step(logits, mask, scaffold_mask, tokens, tau):
     return dict(tokens=tokens, mask=mask, confidences=conf, candidates=cand, n_unmasked=nun, committed=com)
 
 
-def verify_step(ar_logits, mask, scaffold_mask, draft, tokens):
+def verify_step(ar_logits, mask, scaffold_mask, draft, tokens, temperature=0.0, seed=0):
     """Accept scan of scaffold speculative decoding; inputs are not modified.
+    ``temperature`` = 0: greedy verifier; > 0: sampled verifier (Gumbel-max
+    with the Philox stream of ``seed``).
 
     Returns dict(tokens, mask, ar_tokens, n_accepted, accepted).
     """
@@ -138,11 +150,33 @@ def verify_step(ar_logits, mask, scaffold_mask, draft, tokens):
     ar = np.empty((N, B), dtype=np.int32)
     nacc = np.empty((N,), dtype=np.int32)
     acc = np.empty((N, B), dtype=np.uint8)
-    rc = _load().fddo_verify_step(N, B, V, dt, _ptr(ar_logits), _ptr(sc), _ptr(draft), _ptr(mask), _ptr(tokens),
-                                  _ptr(ar), _ptr(nacc), _ptr(acc))
+    rc = _load().fddo_verify_step_ex(N, B, V, dt, _ptr(ar_logits), _ptr(sc), _ptr(draft), _ptr(mask),
+                                     _ptr(tokens), _ptr(ar), _ptr(nacc), _ptr(acc), float(temperature), int(seed))
     if rc:
-        raise ValueError("fddo_verify_step rejected its arguments")
+        raise ValueError("fddo_verify_step_ex rejected its arguments")
     return dict(tokens=tokens, mask=mask, ar_tokens=ar, n_accepted=nacc, accepted=acc)
+
+
+def philox4x32_10(counter, key):
+    """One block of the sampler's counter-based generator: 4 + 2 words in, 4 words out."""
+    c = (ctypes.c_uint32 * 4)(*[int(x) for x in counter])
+    k = (ctypes.c_uint32 * 2)(*[int(x) for x in key])
+    out = (ctypes.c_uint32 * 4)()
+    _load().fddo_philox4x32_10(c, k, out)
+    return [int(x) for x in out]
+
+
+def flog2(x):
+    """The sampler's fp32 log2, element by element."""
+    lib = _load()
+    x = np.asarray(x, dtype=np.float32)
+    return np.array([lib.fddo_flog2(float(v)) for v in x.ravel()], dtype=np.float32).reshape(x.shape)
+
+
+def sample_key(x, temperature, seed, row, v):
+    """The sampler's key of one vocabulary entry (fp32)."""
+    lib = _load()
+    return lib.fddo_sample_key(float(x), lib.fddo_sample_scale(float(temperature)), int(seed), int(row), int(v))
 
 
 def block_kv_update(tokens, committed, table_k, table_v, block_k, block_v):

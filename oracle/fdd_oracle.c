@@ -34,6 +34,24 @@
  *                       is discarded.  Scaffold positions are auto-accepted
  *                       (step 1) and do not take part.
  *
+ *  fddo_verify_step_ex  The same rule with a sampled verifier (paper,
+ *                       "Trajectory-only stochasticity": the verifier samples
+ *                       from the softmax in the trajectory section, which is
+ *                       what makes forked rollouts differ).  The paper names
+ *                       no sampling algorithm; the one used is the Gumbel-max
+ *                       form of softmax sampling at temperature T, token =
+ *                       arg max_v (x_v / T + g_v) with g_v standard Gumbel
+ *                       noise, which is an exact sampler of softmax(x / T).
+ *                       So that a sampled token is one well-defined integer,
+ *                       the noise and the comparison are DEFINED in fp32
+ *                       arithmetic (fddo_sample_key below: a counter-based
+ *                       generator, Philox-4x32-10 of Salmon et al., SC'11,
+ *                       keyed by the seed and counted by (row, vocabulary id),
+ *                       and a polynomial log2 made of exactly rounded fp32
+ *                       operations).  This is the one place where the oracle
+ *                       does not work in fp64: the sampler's precision is part
+ *                       of its definition.
+ *
  *  fddo_unmask_step     One iteration of "iteratively unmasks value
  *                       positions" (paper, "Section Diffusion (SD)") under the
  *                       masked-diffusion rule that visible tokens stay fixed
@@ -58,7 +76,10 @@
  * textbook causal attention for B=1, a library softmax-attention with an
  * explicit mask, closed forms, logsumexp from scipy, and the invariants of
  * the unmask rule.  fddo_block_kv_update and fddo_fork_block are pure copies
- * and are pinned by direct comparison with numpy indexing.
+ * and are pinned by direct comparison with numpy indexing.  The sampler is
+ * pinned by the published known-answer vectors of Philox-4x32-10, by the
+ * accuracy of its log2 against the library's, and by the frequencies of its
+ * samples against softmax(x / T) (tests/test_oracle_sample.py).
  *
  * Element types: 0 = double, 1 = float, 2 = bfloat16 stored as uint16.
  * Stored values are widened exactly to double before any arithmetic.
@@ -240,11 +261,81 @@ int fddo_unmask_step(int N, int B, int64_t V, int dtype, double tau, const void 
  *   n_accepted[n]   positions unmasked in block n by this call
  *   accepted[n,b]   1 = draft accepted, 2 = replaced by the AR token, 0 otherwise (may be NULL)
  */
-int fddo_verify_step(int N, int B, int64_t V, int dtype, const void *ar_logits, const uint8_t *scaffold,
-                     const int32_t *draft, uint8_t *mask, int32_t *tokens, int32_t *ar_tok,
-                     int32_t *n_accepted, uint8_t *accepted)
+/* ---- the sampler's arithmetic (fp32 by definition) ------------------------- */
+
+/* Philox-4x32 with 10 rounds: counter-based generator of Salmon, Moraes, Dror and
+ * Shaw, "Parallel random numbers: as easy as 1, 2, 3" (SC'11). */
+void fddo_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
 {
-    if (N <= 0 || B <= 0 || V <= 0) return 1;
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = (uint32_t)p1;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* log2 of a positive normal float, made of exactly rounded fp32 operations:
+ * x = m 2^e with m in [1/sqrt 2, sqrt 2), log2 x = e + f P(f), f = m - 1,
+ * P of degree 8.  Absolute error below 1e-7 on the reduced range. */
+float fddo_flog2(float x)
+{
+    uint32_t bits;
+    memcpy(&bits, &x, 4);
+    int e = (int)((bits >> 23) & 255u) - 127;
+    const uint32_t mb = (bits & 0x7fffffu) | 0x3f800000u;
+    float m;
+    memcpy(&m, &mb, 4);
+    if (m > 1.41421354f) { m = m * 0.5f; e += 1; }
+    const float f = m - 1.0f;
+    float p = 0.12614846229553223f;
+    p = fmaf(p, f, -0.20742103457450867f);
+    p = fmaf(p, f, 0.21566985547542572f);
+    p = fmaf(p, f, -0.23892034590244293f);
+    p = fmaf(p, f, 0.2879183292388916f);
+    p = fmaf(p, f, -0.36070483922958374f);
+    p = fmaf(p, f, 0.48091059923171997f);
+    p = fmaf(p, f, -0.7213473320007324f);
+    p = fmaf(p, f, 1.4426950216293335f);
+    return fmaf(f, p, (float)e);
+}
+
+/* Gumbel-max key of vocabulary entry v of row `row` (= n B + b), in log2 units:
+ *   r   = word (v mod 4) of Philox(counter = (v div 4, row, 0, 0), key = seed)
+ *   u   = ((r >> 9) + 1/2) 2^-23          in (0, 1), exact in fp32
+ *   key = x c - log2(-log2 u)             c = log2(e) / T rounded to fp32
+ * arg max_v key samples softmax(x / T): -ln(-ln u) is standard Gumbel noise and
+ * the change of logarithm base shifts every key by the same constant. */
+float fddo_sample_key(float x, float c, uint64_t seed, uint32_t row, int64_t v)
+{
+    const uint32_t ctr[4] = {(uint32_t)(v >> 2), row, 0u, 0u};
+    const uint32_t key[2] = {(uint32_t)seed, (uint32_t)(seed >> 32)};
+    uint32_t r[4];
+    fddo_philox4x32_10(ctr, key, r);
+    const float u = ((float)(r[v & 3] >> 9) + 0.5f) * 1.1920928955078125e-07f;
+    const float a = -fddo_flog2(u);
+    const float g = -fddo_flog2(a);
+    return fmaf(x, c, g);
+}
+
+float fddo_sample_scale(float temperature) { return (float)(1.4426950408889634 / (double)temperature); }
+
+/* temperature == 0: greedy verifier (arg max of the logits); temperature > 0:
+ * sampled verifier as defined above.  ar_tok receives the verifier's token. */
+int fddo_verify_step_ex(int N, int B, int64_t V, int dtype, const void *ar_logits, const uint8_t *scaffold,
+                        const int32_t *draft, uint8_t *mask, int32_t *tokens, int32_t *ar_tok,
+                        int32_t *n_accepted, uint8_t *accepted, float temperature, uint64_t seed)
+{
+    if (N <= 0 || B <= 0 || V <= 0 || !(temperature >= 0.0f)) return 1;
+    const float c = temperature > 0.0f ? fddo_sample_scale(temperature) : 0.0f;
     for (int n = 0; n < N; ++n) {
         int count = 0, rejected = 0;
         for (int b = 0; b < B; ++b) {
@@ -254,11 +345,19 @@ int fddo_verify_step(int N, int B, int64_t V, int dtype, const void *ar_logits, 
             if (ar_tok) ar_tok[i] = -1;
             if (!is_draft) continue;
             const size_t base = (size_t)i * (size_t)V;
-            double xmax = widen(ar_logits, dtype, base);
             int64_t arg = 0;
-            for (int64_t v = 1; v < V; ++v) {
-                const double x = widen(ar_logits, dtype, base + v);
-                if (x > xmax) { xmax = x; arg = v; }
+            if (temperature > 0.0f) {
+                float kmax = fddo_sample_key((float)widen(ar_logits, dtype, base), c, seed, (uint32_t)i, 0);
+                for (int64_t v = 1; v < V; ++v) {
+                    const float k = fddo_sample_key((float)widen(ar_logits, dtype, base + v), c, seed, (uint32_t)i, v);
+                    if (k > kmax) { kmax = k; arg = v; }
+                }
+            } else {
+                double xmax = widen(ar_logits, dtype, base);
+                for (int64_t v = 1; v < V; ++v) {
+                    const double x = widen(ar_logits, dtype, base + v);
+                    if (x > xmax) { xmax = x; arg = v; }
+                }
             }
             if (ar_tok) ar_tok[i] = (int32_t)arg;
             if (rejected) continue;                 /* discarded: stays masked */
@@ -273,6 +372,14 @@ int fddo_verify_step(int N, int B, int64_t V, int dtype, const void *ar_logits, 
         if (n_accepted) n_accepted[n] = count;
     }
     return 0;
+}
+
+int fddo_verify_step(int N, int B, int64_t V, int dtype, const void *ar_logits, const uint8_t *scaffold,
+                     const int32_t *draft, uint8_t *mask, int32_t *tokens, int32_t *ar_tok,
+                     int32_t *n_accepted, uint8_t *accepted)
+{
+    return fddo_verify_step_ex(N, B, V, dtype, ar_logits, scaffold, draft, mask, tokens, ar_tok, n_accepted, accepted,
+                               0.0f, 0u);
 }
 
 /* K/V rows of just-committed positions <- table row (token mod T). */
