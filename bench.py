@@ -36,6 +36,8 @@ if ROOT not in sys.path:
 # Published MI355X peaks
 PEAK_HBM_GBS = 8000.0
 PEAK_BF16_TFLOPS = 2500.0
+PEAK_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12      # one 32-bit vector operation per lane and clock
+SAMPLER_OPS_PER_ENTRY = 64                         # Philox share 20, uniform 4, two log2 36, key and compare 4
 STEPS_PER_BLOCK = 8
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each scaled
 # by what the same counter reads for a 1 GiB device copy (0.5x and 1.0x); summary and commands in
@@ -169,6 +171,19 @@ def time_spec_verify(F, w, d, g, logits, steps, warmup):
     ms = t0.elapsed_time(t1) / steps
     attn_ms = ev.mean_ms(steps)
     ver_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(v0, v1)]))
+    # the sampled verifier of the trajectory section on the same rows
+    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_samp = max(4, steps // 5)
+    for i in range(n_samp + 2):
+        for k in ("tokens", "mask"):
+            F.fdd_fork_block(parent[k], w.N, dst=st[k])
+        if i == 2:
+            s0.record()
+        F.fdd_verify_step(logits[i % 2], st["mask"], scaffold, draft, st["tokens"], nacc, acc, workspace=ws_u,
+                          temperature=1.0, seed=1000 + i)
+    s1.record()
+    torch.cuda.synchronize()
+    samp_ms = s0.elapsed_time(s1) / n_samp
     elig = int(((d["mask"][0] == 1) & (d["scaffold_mask"][0] == 0)).sum()) * w.N
     byt = elig * w.V * 2
     # causal tail: position b sees L + b + 1 keys
@@ -181,6 +196,13 @@ def time_spec_verify(F, w, d, g, logits, steps, warmup):
         "verify_call_us": round(ver_ms * 1e3, 2), "verify_rows": elig,
         "verify_GBs": round(byt / (ver_ms * 1e-3) / 1e9, 1),
         "verify_frac_peak_hbm": round(byt / (ver_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        # Gumbel-max sampling is bound by the vector ALUs: 64 vector operations per vocabulary entry by the
+        # sampler's definition, against 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+        "sampled_verify_call_us": round(samp_ms * 1e3, 2),
+        "sampled_verify": {"bound": "alu", "unit": "Tops/s", "peak": PEAK_VALU_TOPS,
+                           "achieved": round(elig * w.V * SAMPLER_OPS_PER_ENTRY / (samp_ms * 1e-3) / 1e12, 2),
+                           "frac": round(elig * w.V * SAMPLER_OPS_PER_ENTRY / (samp_ms * 1e-3) / 1e12 / PEAK_VALU_TOPS, 4),
+                           "entries_per_call": elig * w.V, "ops_per_entry": SAMPLER_OPS_PER_ENTRY},
     }
 
 

@@ -185,12 +185,32 @@ fdd_status fdd_unmask_step(const fdd_unmask_params *p);
  * n_accepted[n] counts the positions unmasked by this call; accepted[n,b] is
  * 1 for an accepted draft, 2 for the replaced position, 0 otherwise.
  * Only the logits rows of draft positions are read.
+ *
+ * Sampled verifier (paper, "Trajectory-only stochasticity": in the trajectory
+ * section the verifier samples from its softmax, which is what makes forked
+ * rollouts differ).  With temperature > 0 the verifier's token at a draft
+ * position is a sample of softmax(ar_logits[n,b,:] / temperature) instead of
+ * the arg max, drawn by the Gumbel-max rule
+ *     token = lowest id attaining max_v key(v),
+ *     key(v) = fma(x_v, c, -flog2(-flog2(u_v)))          (binary32 throughout)
+ *     c   = (float)(log2(e) / (double)temperature)
+ *     u_v = ((r_v >> 9) + 0.5) * 2^-23
+ *     r_v = word (v mod 4) of Philox-4x32-10(counter = (v div 4, n*B + b, 0, 0),
+ *                                            key = (seed low word, seed high word))
+ *     flog2(y) = e + f P(f) for y = m 2^e, m in [1/sqrt 2, sqrt 2), f = m - 1, with
+ *                the degree-8 polynomial P listed in csrc/unmask.hip, evaluated
+ *                by Horner's rule in fused multiply-adds.
+ * Every step is an exactly rounded binary32 operation, so a (seed, row, logits)
+ * triple names one token on any conforming implementation.  The same seed
+ * gives the same tokens; rollouts differ because their rows n*B + b differ.
+ * temperature == 0 selects the greedy verifier; negative or non-finite values
+ * are rejected with FDD_ERR_UNSUPPORTED.
  */
 typedef struct fdd_verify_params {
     int32_t N, B;
     int64_t V;
     int32_t dtype;                 /* fdd_dtype of ar_logits */
-    int32_t reserved;              /* must be 0 */
+    float temperature;             /* 0 = greedy verifier, > 0 = sampled verifier */
     const void *ar_logits;         /* [N,B,V] */
     const uint8_t *scaffold_mask;  /* [N,B]; may be NULL */
     const int32_t *draft;          /* [N,B] draft tokens (read at draft positions only) */
@@ -201,6 +221,7 @@ typedef struct fdd_verify_params {
     void *workspace;               /* >= fdd_verify_workspace() bytes */
     size_t workspace_bytes;
     void *stream;
+    uint64_t seed;                 /* sampled verifier: key of the random stream */
 } fdd_verify_params;
 
 size_t fdd_verify_workspace(const fdd_verify_params *p);

@@ -45,10 +45,11 @@ class UnmaskParams(C.Structure):
 
 
 class VerifyParams(C.Structure):
-    _fields_ = [("N", C.c_int32), ("B", C.c_int32), ("V", C.c_int64), ("dtype", C.c_int32), ("reserved", C.c_int32),
+    _fields_ = [("N", C.c_int32), ("B", C.c_int32), ("V", C.c_int64), ("dtype", C.c_int32), ("temperature", C.c_float),
                 ("ar_logits", C.c_void_p), ("scaffold_mask", C.c_void_p), ("draft", C.c_void_p), ("mask", C.c_void_p),
                 ("tokens", C.c_void_p), ("n_accepted", C.c_void_p), ("accepted", C.c_void_p),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p),
+                ("seed", C.c_uint64)]
 
 
 class KvUpdateParams(C.Structure):
@@ -279,9 +280,10 @@ def fdd_unmask_step(logits, mask, scaffold_mask, tau, tokens, confidences=None, 
 
 
 def fdd_verify_step(ar_logits, mask, scaffold_mask, draft, tokens, n_accepted=None, accepted=None, workspace=None,
-                    stream=None):
+                    stream=None, temperature=0.0, seed=0):
     """Accept scan of scaffold speculative decoding; ``tokens`` and ``mask`` are
-    updated in place.  Returns (tokens, n_accepted, accepted)."""
+    updated in place.  ``temperature`` > 0 selects the sampled verifier with the
+    random stream ``seed``.  Returns (tokens, n_accepted, accepted)."""
     import torch
     lib = load_library()
     N, B, V = ar_logits.shape
@@ -295,6 +297,7 @@ def fdd_verify_step(ar_logits, mask, scaffold_mask, draft, tokens, n_accepted=No
         accepted = torch.empty((N, B), dtype=torch.uint8, device=dev)
     p = VerifyParams()
     p.N, p.B, p.V, p.dtype = N, B, V, _dtype_code(ar_logits)
+    p.temperature, p.seed = float(temperature), int(seed)
     p.ar_logits = _dev(ar_logits, "ar_logits")
     p.scaffold_mask = _dev(scaffold_mask, "scaffold_mask")
     p.draft, p.mask, p.tokens = _dev(draft, "draft"), _dev(mask, "mask"), _dev(tokens, "tokens")

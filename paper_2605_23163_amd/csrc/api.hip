@@ -258,7 +258,8 @@ fdd_status fdd_verify_step(const fdd_verify_params* p)
     if (p->V >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_verify_step: V must be below 2^31");
     if ((long long)p->N * p->B > (1ll << 24)) return fail(FDD_ERR_SHAPE, "fdd_verify_step: N*B too large");
     if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_verify_step: dtype %d is neither FDD_F32 nor FDD_BF16", p->dtype);
-    if (p->reserved != 0) return fail(FDD_ERR_UNSUPPORTED, "fdd_verify_step: reserved field must be 0");
+    if (!(p->temperature >= 0.f) || std::isinf(p->temperature))
+        return fail(FDD_ERR_UNSUPPORTED, "fdd_verify_step: temperature must be 0 (greedy) or positive and finite");
     if (!p->ar_logits || !p->draft || !p->mask || !p->tokens)
         return fail(FDD_ERR_NULL, "fdd_verify_step: ar_logits, draft, mask and tokens must not be NULL");
     if (!aligned16(p->ar_logits)) return fail(FDD_ERR_UNSUPPORTED, "fdd_verify_step: ar_logits must be 16-byte aligned");

@@ -18,6 +18,11 @@
 //                 stored values (frequent in bf16) always resolve to the
 //                 lowest id.  Workgroups of non-eligible rows exit at once
 //                 and read nothing.
+//   vocab_sample  the sampled verifier's sibling of vocab_reduce: the value
+//                 reduced is the Gumbel-max key of every vocabulary entry
+//                 (a Philox-4x32-10 word per entry, two polynomial log2, one
+//                 fused multiply-add), so the pass is bound by the vector ALUs
+//                 rather than by HBM.
 //   block_select  one workgroup per rollout: merges the pieces of each
 //                 position in a fixed order (sum finished in fp64), applies
 //                 the tau test and the forced single commit, and writes
@@ -58,6 +63,8 @@ struct Args {
     int N, B, vsplits;
     long long V;
     float tau;
+    float c;                // sampled verifier: log2(e) / temperature
+    uint32_t seed_lo, seed_hi;
 };
 
 struct Run {
@@ -201,6 +208,159 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
         p.m = t.m;
         p.arg = t.idx;
         p.s = t.s;
+        p.pad = 0;
+        a.ws[(size_t)row * a.vsplits + piece] = p;
+    }
+}
+
+// ---- sampled verifier ------------------------------------------------------
+// The arithmetic below is the definition of the sampler (see fdd_verify_step
+// in the public header): every operation is written out as one exactly
+// rounded binary32 operation and must not be contracted or reassociated.
+
+// Philox-4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw: "Parallel random
+// numbers: as easy as 1, 2, 3", SC'11): counter (c0, c1, 0, 0), key (k0, k1).
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    uint32_t c2 = 0u, c3 = 0u;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// log2 of a positive normal float: x = m 2^e, m in [1/sqrt 2, sqrt 2), e + f P(f) with f = m - 1
+__device__ __forceinline__ float flog2_def(float x)
+{
+    const uint32_t bits = __float_as_uint(x);
+    int e = (int)((bits >> 23) & 255u) - 127;
+    float m = __uint_as_float((bits & 0x7fffffu) | 0x3f800000u);
+    if (m > 1.41421354f) { m = __fmul_rn(m, 0.5f); e += 1; }
+    const float f = __fsub_rn(m, 1.0f);
+    float p = 0.12614846229553223f;
+    p = __fmaf_rn(p, f, -0.20742103457450867f);
+    p = __fmaf_rn(p, f, 0.21566985547542572f);
+    p = __fmaf_rn(p, f, -0.23892034590244293f);
+    p = __fmaf_rn(p, f, 0.2879183292388916f);
+    p = __fmaf_rn(p, f, -0.36070483922958374f);
+    p = __fmaf_rn(p, f, 0.48091059923171997f);
+    p = __fmaf_rn(p, f, -0.7213473320007324f);
+    p = __fmaf_rn(p, f, 1.4426950216293335f);
+    return __fmaf_rn(f, p, (float)e);
+}
+
+__device__ __forceinline__ float gumbel_key(float x, float c, uint32_t r)
+{
+    const float u = __fmul_rn(__fadd_rn((float)(r >> 9), 0.5f), 1.1920928955078125e-07f);
+    const float a = -flog2_def(u);
+    const float g = -flog2_def(a);
+    return __fmaf_rn(x, c, g);
+}
+
+struct Best {
+    float k;
+    int idx;
+};
+__device__ __forceinline__ void take(Best& a, float k, int idx)
+{
+    if (k > a.k || (k == a.k && idx < a.idx)) { a.k = k; a.idx = idx; }
+}
+
+// Same work split as vocab_reduce; leaves (largest key, lowest id attaining it) per piece.
+template <typename T>
+__global__ __launch_bounds__(RTHREADS) void vocab_sample_kernel(Args a)
+{
+    constexpr int VEC = 16 / sizeof(T);
+    const int row = blockIdx.x / a.vsplits;
+    if (a.mask[row] != 1 || (a.scaffold && a.scaffold[row])) return;
+    const int piece = blockIdx.x % a.vsplits;
+    const long long per = (a.V + a.vsplits - 1) / a.vsplits;
+    const long long v_lo = piece * per;
+    const long long v_hi = min(a.V, v_lo + per);
+    const T* base = static_cast<const T*>(a.logits) + (size_t)row * (size_t)a.V;
+    const int tid = threadIdx.x;
+    Best r;
+    r.k = -INFINITY;
+    r.idx = 0x7fffffff;
+
+    auto one = [&](long long v) {     // a single entry: its own generator block
+        const float x = sizeof(T) == 2 ? bf16_to_f32(((const uint16_t*)base)[v]) : ((const float*)base)[v];
+        uint32_t w[4];
+        philox4x32_10((uint32_t)(v >> 2), (uint32_t)row, a.seed_lo, a.seed_hi, w);
+        take(r, gumbel_key(x, a.c, w[v & 3]), (int)v);
+    };
+    if (v_lo < v_hi) {
+        const size_t e_lo = (size_t)row * (size_t)a.V + (size_t)v_lo;
+        long long head = (long long)((VEC - (e_lo % VEC)) % VEC);
+        if (head > v_hi - v_lo) head = v_hi - v_lo;
+        const long long body0 = v_lo + head;
+        const long long nvec = (v_hi - body0) / VEC;
+        const long long tail0 = body0 + nvec * VEC;
+        if (tid < head) one(v_lo + tid);
+        const u32x4* vp = reinterpret_cast<const u32x4*>(base + body0);
+        const bool quads = (body0 & 3) == 0;      // a 16-byte vector then holds whole generator blocks
+        for (long long i = tid; i < nvec; i += RTHREADS) {
+            const u32x4 raw = __builtin_nontemporal_load(vp + i);
+            const long long v0 = body0 + i * VEC;
+            float x[VEC];
+            if (sizeof(T) == 2) {
+                const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    x[2 * j] = __uint_as_float(w[j] << 16);
+                    x[(2 * j + 1) % VEC] = __uint_as_float(w[j] & 0xffff0000u);
+                }
+            } else {
+                x[0] = __uint_as_float(raw.x);
+                x[1] = __uint_as_float(raw.y);
+                x[2 % VEC] = __uint_as_float(raw.z);
+                x[3 % VEC] = __uint_as_float(raw.w);
+            }
+            if (quads) {
+#pragma unroll
+                for (int q = 0; q < VEC / 4; ++q) {
+                    uint32_t w[4];
+                    philox4x32_10((uint32_t)((v0 >> 2) + q), (uint32_t)row, a.seed_lo, a.seed_hi, w);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) take(r, gumbel_key(x[q * 4 + j], a.c, w[j]), (int)(v0 + q * 4 + j));
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < VEC; ++j) {
+                    uint32_t w[4];
+                    philox4x32_10((uint32_t)((v0 + j) >> 2), (uint32_t)row, a.seed_lo, a.seed_hi, w);
+                    take(r, gumbel_key(x[j], a.c, w[(v0 + j) & 3]), (int)(v0 + j));
+                }
+            }
+        }
+        const long long ntail = v_hi - tail0;
+        if (tid < ntail) one(tail0 + tid);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const float ok = __shfl_xor(r.k, off, 64);
+        const int oi = __shfl_xor(r.idx, off, 64);
+        take(r, ok, oi);
+    }
+    __shared__ Best part[RTHREADS / 64];
+    if ((tid & 63) == 0) part[tid >> 6] = r;
+    __syncthreads();
+    if (tid == 0) {
+        Best t = part[0];
+#pragma unroll
+        for (int w = 1; w < RTHREADS / 64; ++w) take(t, part[w].k, part[w].idx);
+        Partial p;
+        p.m = t.k;
+        p.arg = t.idx;
+        p.s = 0.f;
         p.pad = 0;
         a.ws[(size_t)row * a.vsplits + piece] = p;
     }
@@ -352,6 +512,7 @@ hipError_t launch_unmask(const fdd_unmask_params& p, const UnmaskPlan& plan, hip
     a.ws = static_cast<Partial*>(p.workspace);
     a.draft = nullptr;
     a.N = p.N; a.B = p.B; a.vsplits = plan.vsplits; a.V = p.V; a.tau = p.tau;
+    a.c = 0.f; a.seed_lo = 0u; a.seed_hi = 0u;
     const dim3 grid((unsigned)(plan.vsplits * p.N * p.B));
     if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_reduce_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
     else hipLaunchKernelGGL(vocab_reduce_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
@@ -374,9 +535,17 @@ hipError_t launch_verify(const fdd_verify_params& p, const UnmaskPlan& plan, hip
     a.ws = static_cast<Partial*>(p.workspace);
     a.draft = p.draft;
     a.N = p.N; a.B = p.B; a.vsplits = plan.vsplits; a.V = p.V; a.tau = 0.f;
+    a.c = p.temperature > 0.f ? (float)(1.4426950408889634 / (double)p.temperature) : 0.f;
+    a.seed_lo = (uint32_t)p.seed;
+    a.seed_hi = (uint32_t)(p.seed >> 32);
     const dim3 grid((unsigned)(plan.vsplits * p.N * p.B));
-    if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_reduce_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
-    else hipLaunchKernelGGL(vocab_reduce_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
+    if (p.temperature > 0.f) {
+        if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_sample_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
+        else hipLaunchKernelGGL(vocab_sample_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
+    } else {
+        if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_reduce_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
+        else hipLaunchKernelGGL(vocab_reduce_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(verify_scan_kernel, dim3(p.N), dim3(STHREADS), 0, s, a);

@@ -118,7 +118,7 @@ def test_verify_workspace_and_errors(lib):
         return p
     assert lib.fdd_verify_workspace(C.byref(vp())) == lib.fdd_unmask_workspace(C.byref(unmask()))
     assert lib.fdd_verify_workspace(C.byref(vp(V=0))) == 0
-    for kw, code in [(dict(N=0), 2), (dict(V=1 << 31), 2), (dict(dtype=5), 3), (dict(reserved=1), 4), (dict(draft=None), 1),
+    for kw, code in [(dict(N=0), 2), (dict(V=1 << 31), 2), (dict(dtype=5), 3), (dict(temperature=-1.0), 4), (dict(temperature=float('nan')), 4), (dict(temperature=float('inf')), 4), (dict(draft=None), 1),
                      (dict(ar_logits=None), 1), (dict(ar_logits=264), 4), (dict(workspace=None), 5), (dict(workspace_bytes=1), 5)]:
         assert lib.fdd_verify_step(C.byref(vp(**kw))) == code, kw
         assert lib.fdd_last_error().decode().startswith("fdd_verify_step:")

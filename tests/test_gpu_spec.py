@@ -1,5 +1,6 @@
 """GPU parity of the scaffold-speculative-decoding pieces against the oracle:
-causal in-block attention (verify pass) and the accept scan."""
+causal in-block attention (verify pass), the accept scan, and the sampled
+verifier of the trajectory section."""
 import numpy as np
 import pytest
 import torch
@@ -101,3 +102,62 @@ def test_draft_then_verify_block(F, oracle):
     np.testing.assert_array_equal(m.cpu().numpy(), v["mask"])
     np.testing.assert_array_equal(nacc.cpu().numpy(), v["n_accepted"])
     assert np.all(t.cpu().numpy()[scaffold == 1] == 7)
+
+
+@pytest.mark.parametrize("case", [(3, 9, 999, W.BF16, 0.9, 1), (2, 33, 20011, W.BF16, 1.3, 2 ** 40 + 7), (4, 8, 152064, W.BF16, 0.7, 3),
+                                  (2, 70, 5000, W.F32, 1.0, 4), (5, 6, 37, W.F32, 2.0, 5), (3, 12, 4096, W.BF16, 0.25, 2 ** 63 + 11),
+                                  (2, 5, 1003, W.F32, 1.0, 6), (2, 5, 1001, W.BF16, 1e-6, 7)])
+def test_sampled_verifier_is_bit_exact(F, oracle, case):
+    # the sampler is defined in binary32 arithmetic on both sides: the sampled tokens,
+    # and with them every accept decision, must agree exactly
+    N, B, V, dtype, temperature, seed = case
+    print_case(test="spec_sampled_verify", case=case)
+    rng = np.random.default_rng(hash(case[:3]) % 2**32 + 9)
+    logits, mask, scaffold, _, tokens = synth(rng, N, B, V, dtype, 0.0)
+    none = np.full((N, B), -1, dtype=np.int32)
+    sampled = oracle.verify_step(logits, mask, scaffold, none, tokens, temperature=temperature, seed=seed)["ar_tokens"]
+    # drafts that agree with the sampled tokens on most positions
+    draft = np.where(rng.random((N, B)) < 0.85, sampled, (sampled + 1) % V).astype(np.int32)
+    ref = oracle.verify_step(logits, mask, scaffold, draft, tokens, temperature=temperature, seed=seed)
+    m, t = torch.from_numpy(mask.copy()).cuda(), torch.from_numpy(tokens.copy()).cuda()
+    _, nacc, acc = F.fdd_verify_step(to_dev(logits), m, torch.from_numpy(scaffold).cuda(), torch.from_numpy(draft).cuda(), t,
+                                     temperature=temperature, seed=seed)
+    # all sampled tokens, not only those the scan reaches: verify against drafts that never match
+    m2, t2 = torch.from_numpy(mask.copy()).cuda(), torch.from_numpy(tokens.copy()).cuda()
+    first = np.zeros((N, B), dtype=bool)
+    elig = (mask == 1) & (scaffold == 0)
+    for n in range(N):
+        idx = np.nonzero(elig[n])[0]
+        if len(idx):
+            first[n, idx[0]] = True
+    F.fdd_verify_step(to_dev(logits), m2, torch.from_numpy(scaffold).cuda(), torch.from_numpy(none).cuda(), t2,
+                      temperature=temperature, seed=seed)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t.cpu().numpy(), ref["tokens"])
+    np.testing.assert_array_equal(m.cpu().numpy(), ref["mask"])
+    np.testing.assert_array_equal(nacc.cpu().numpy(), ref["n_accepted"])
+    np.testing.assert_array_equal(acc.cpu().numpy(), ref["accepted"])
+    np.testing.assert_array_equal(t2.cpu().numpy()[first], sampled[first])
+    # sampling is not the arg max (except at the near-zero temperature case)
+    greedy = W.widen(logits, dtype).argmax(-1)
+    if temperature > 0.1:
+        assert np.mean(sampled[elig] == greedy[elig]) < 0.9
+    print(f"accepted per block: {ref['n_accepted'].tolist()}")
+
+
+def test_sampled_tokens_of_every_row_match_oracle(F, oracle):
+    # one draft position per block, so that the scan exposes the sampled token of every row
+    print_case(test="spec_sampled_rows")
+    rng = np.random.default_rng(21)
+    N, B, V = 64, 4, 3000
+    logits = W.to_storage((rng.standard_normal((N, B, V)) * 2).astype(np.float32), W.BF16)
+    mask = np.zeros((N, B), dtype=np.uint8)
+    mask[np.arange(N), rng.integers(0, B, N)] = 1
+    none = np.full((N, B), -1, dtype=np.int32)
+    tokens = np.zeros((N, B), dtype=np.int32)
+    ref = oracle.verify_step(logits, mask, None, none, tokens, temperature=0.8, seed=99)
+    m, t = torch.from_numpy(mask.copy()).cuda(), torch.from_numpy(tokens.copy()).cuda()
+    F.fdd_verify_step(to_dev(logits), m, None, torch.from_numpy(none).cuda(), t, temperature=0.8, seed=99)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t.cpu().numpy(), ref["tokens"])
+    assert len(set(ref["tokens"][mask == 1].tolist())) > 30
