@@ -41,6 +41,11 @@ def _load():
         lib.fddo_block_attn.argtypes = [c.c_int] * 7 + [c.c_double] + [c.c_void_p] * 6 + [c.c_int64, c.c_void_p]
         lib.fddo_block_attn_ex.restype = c.c_int
         lib.fddo_block_attn_ex.argtypes = [c.c_int] * 7 + [c.c_double, c.c_int] + [c.c_void_p] * 6 + [c.c_int64, c.c_void_p]
+        lib.fddo_block_attn_ext.restype = c.c_int
+        lib.fddo_block_attn_ext.argtypes = ([c.c_int] * 9 + [c.c_double, c.c_int] + [c.c_void_p] * 8 +
+                                            [c.c_int64, c.c_void_p])
+        lib.fddo_block_commit.restype = c.c_int
+        lib.fddo_block_commit.argtypes = [c.c_int] * 7 + [c.c_void_p] * 4
         lib.fddo_verify_step.restype = c.c_int
         lib.fddo_verify_step.argtypes = [c.c_int, c.c_int, c.c_int64, c.c_int] + [c.c_void_p] * 8
         lib.fddo_verify_step_ex.restype = c.c_int
@@ -82,9 +87,12 @@ def _same_storage(*arrs):
     return arrs, _DT[dt]
 
 
-def block_attn(q, prefix_k, prefix_v, block_k, block_v, scale=None, rows=None, causal_block=False):
+def block_attn(q, prefix_k, prefix_v, block_k, block_v, scale=None, rows=None, causal_block=False,
+               ext_k=None, ext_v=None, E=0):
     """Block-causal shared-prefix attention in fp64.  ``causal_block=True`` makes
     the in-block part causal (the verify pass of scaffold speculative decoding).
+    ``ext_k/ext_v`` [N,Ecap,Hkv,D] with ``E`` valid rows per rollout: the blocks a
+    rollout has committed since the fork, visible to that rollout only.
 
     q [N,B,Hq,D], prefix_k/v [L,Hkv,D], block_k/v [N,B,Hkv,D]; float64,
     float32, or uint16 holding bf16 bits.  ``rows``: optional int array
@@ -103,8 +111,16 @@ def block_attn(q, prefix_k, prefix_v, block_k, block_v, scale=None, rows=None, c
         r = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1, 3)
         nr = r.shape[0]
         out = np.empty((nr, D), dtype=np.float64)
-    rc = _load().fddo_block_attn_ex(N, B, L, Hq, Hkv, D, dt, scale, int(bool(causal_block)), _ptr(q), _ptr(prefix_k),
-                                    _ptr(prefix_v), _ptr(block_k), _ptr(block_v), _ptr(r), nr, _ptr(out))
+    Ecap = 0
+    if E > 0:
+        (ext_k, ext_v), dte = _same_storage(ext_k, ext_v)
+        assert dte == dt and ext_k.shape == ext_v.shape and ext_k.shape[0] == N and ext_k.shape[2:] == (Hkv, D)
+        Ecap = ext_k.shape[1]
+    else:
+        ext_k = ext_v = None
+    rc = _load().fddo_block_attn_ext(N, B, L, int(E), Ecap, Hq, Hkv, D, dt, scale, int(bool(causal_block)), _ptr(q),
+                                     _ptr(prefix_k), _ptr(prefix_v), _ptr(ext_k), _ptr(ext_v), _ptr(block_k),
+                                     _ptr(block_v), _ptr(r), nr, _ptr(out))
     if rc:
         raise ValueError("fddo_block_attn rejected its arguments")
     return out
@@ -192,6 +208,18 @@ def block_kv_update(tokens, committed, table_k, table_v, block_k, block_v):
     if rc:
         raise ValueError("fddo_block_kv_update rejected its arguments")
     return block_k, block_v
+
+
+def block_commit(block_k, block_v, ext_k, ext_v, E):
+    """Returns copies of (ext_k, ext_v) with rows E .. E+B-1 of every rollout set to its block."""
+    (block_k, block_v, ext_k, ext_v), dt = _same_storage(block_k, block_v, ext_k, ext_v)
+    ext_k, ext_v = ext_k.copy(), ext_v.copy()
+    N, B, Hkv, D = block_k.shape
+    rc = _load().fddo_block_commit(N, B, int(E), ext_k.shape[1], Hkv, D, dt, _ptr(block_k), _ptr(block_v), _ptr(ext_k),
+                                   _ptr(ext_v))
+    if rc:
+        raise ValueError("fddo_block_commit rejected its arguments")
+    return ext_k, ext_v
 
 
 def fork_block(src, N):

@@ -26,6 +26,19 @@
  *                       Decoding (paper, "Scaffold Speculative Decoding (SS)",
  *                       step 3: "a causal forward pass over the entire block").
  *
+ *  fddo_block_attn_ext  The same attention when a rollout has already finished
+ *                       blocks of its own after the fork (paper, "Shared
+ *                       prefix": the trajectory section is continued N times
+ *                       from the forked cache, and that section spans several
+ *                       blocks; "Block-Causal Diffusion": a block attends
+ *                       causally to ALL earlier blocks).  The keys a row of
+ *                       rollout n sees are then three runs: the shared prefix,
+ *                       the E rows rollout n has committed since the fork
+ *                       (its private extension), and its live block.
+ *
+ *  fddo_block_commit    A finished block joins its rollout's extension: rows
+ *                       E .. E+B-1 of ext[n] become block[n] (a pure copy).
+ *
  *  fddo_verify_step     The accept rule of the same step 3: value positions
  *                       are visited left to right; a draft token equal to the
  *                       arg max of the AR distribution at its position is
@@ -120,10 +133,19 @@ static size_t elem_size(int dtype) { return dtype == 0 ? 8 : dtype == 1 ? 4 : 2;
  * the KV head h / (Hq/Hkv).  rows == NULL: all (n,b,h), out is [N,B,Hq,D].
  * rows != NULL: n_rows triples (n,b,h); out is [n_rows,D].
  */
+int fddo_block_attn_ext(int N, int B, int L, int E, int Ecap, int Hq, int Hkv, int D, int dtype, double scale,
+                        int causal_block, const void *q, const void *prefix_k, const void *prefix_v,
+                        const void *ext_k, const void *ext_v, const void *block_k, const void *block_v,
+                        const int32_t *rows, int64_t n_rows, double *out);
+
 int fddo_block_attn_ex(int N, int B, int L, int Hq, int Hkv, int D, int dtype, double scale, int causal_block,
                        const void *q, const void *prefix_k, const void *prefix_v,
                        const void *block_k, const void *block_v,
-                       const int32_t *rows, int64_t n_rows, double *out);
+                       const int32_t *rows, int64_t n_rows, double *out)
+{
+    return fddo_block_attn_ext(N, B, L, 0, 0, Hq, Hkv, D, dtype, scale, causal_block, q, prefix_k, prefix_v, NULL, NULL,
+                               block_k, block_v, rows, n_rows, out);
+}
 
 int fddo_block_attn(int N, int B, int L, int Hq, int Hkv, int D, int dtype, double scale,
                     const void *q, const void *prefix_k, const void *prefix_v,
@@ -134,15 +156,20 @@ int fddo_block_attn(int N, int B, int L, int Hq, int Hkv, int D, int dtype, doub
                               rows, n_rows, out);
 }
 
-/* causal_block == 0: the whole own block is visible; != 0: block keys up to the query's own position. */
-int fddo_block_attn_ex(int N, int B, int L, int Hq, int Hkv, int D, int dtype, double scale, int causal_block,
-                       const void *q, const void *prefix_k, const void *prefix_v,
-                       const void *block_k, const void *block_v,
-                       const int32_t *rows, int64_t n_rows, double *out)
+/*
+ * Visible keys of a row of rollout n, in order: prefix rows 0..L-1 (shared),
+ * extension rows ext[n, 0..E-1] (ext is [N, Ecap, Hkv, D]), block rows.
+ * causal_block == 0: the whole own block is visible; != 0: block keys up to
+ * the query's own position.
+ */
+int fddo_block_attn_ext(int N, int B, int L, int E, int Ecap, int Hq, int Hkv, int D, int dtype, double scale,
+                        int causal_block, const void *q, const void *prefix_k, const void *prefix_v,
+                        const void *ext_k, const void *ext_v, const void *block_k, const void *block_v,
+                        const int32_t *rows, int64_t n_rows, double *out)
 {
-    if (N <= 0 || B <= 0 || L < 0 || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv) return 1;
+    if (N <= 0 || B <= 0 || L < 0 || E < 0 || E > Ecap || Hq <= 0 || Hkv <= 0 || D <= 0 || Hq % Hkv) return 1;
     const int G = Hq / Hkv;
-    const int Sfull = L + B;
+    const int Sfull = L + E + B;
     const int64_t total = rows ? n_rows : (int64_t)N * B * Hq;
     int bad = 0;
 #pragma omp parallel
@@ -155,19 +182,19 @@ int fddo_block_attn_ex(int N, int B, int L, int Hq, int Hkv, int D, int dtype, d
             else { h = (int)(r % Hq); b = (int)((r / Hq) % B); n = (int)(r / ((int64_t)Hq * B)); }
             if (n < 0 || n >= N || b < 0 || b >= B || h < 0 || h >= Hq) { bad = 1; continue; }
             const int kh = h / G;
-            const int S = causal_block ? L + b + 1 : Sfull;   /* number of visible keys */
+            const int S = causal_block ? L + E + b + 1 : Sfull;   /* number of visible keys */
             const size_t qo = (((size_t)n * B + b) * Hq + h) * D;
-            /* scores over every visible key: the prefix, then the own block */
+            /* key j: which array it lives in and at which element offset */
+            #define FDDO_KEY(j, PK, EK, BK, arr, off) do { \
+                if ((j) < L) { arr = (PK); off = ((size_t)(j) * Hkv + kh) * D; } \
+                else if ((j) < L + E) { arr = (EK); off = (((size_t)n * Ecap + ((j) - L)) * Hkv + kh) * D; } \
+                else { arr = (BK); off = (((size_t)n * B + ((j) - L - E)) * Hkv + kh) * D; } } while (0)
             double smax = -INFINITY;
             for (int j = 0; j < S; ++j) {
+                const void *arr; size_t ko;
+                FDDO_KEY(j, prefix_k, ext_k, block_k, arr, ko);
                 double acc = 0.0;
-                if (j < L) {
-                    const size_t ko = ((size_t)j * Hkv + kh) * D;
-                    for (int d = 0; d < D; ++d) acc += widen(q, dtype, qo + d) * widen(prefix_k, dtype, ko + d);
-                } else {
-                    const size_t ko = (((size_t)n * B + (j - L)) * Hkv + kh) * D;
-                    for (int d = 0; d < D; ++d) acc += widen(q, dtype, qo + d) * widen(block_k, dtype, ko + d);
-                }
+                for (int d = 0; d < D; ++d) acc += widen(q, dtype, qo + d) * widen(arr, dtype, ko + d);
                 s[j] = scale * acc;
                 if (s[j] > smax) smax = s[j];
             }
@@ -177,18 +204,28 @@ int fddo_block_attn_ex(int N, int B, int L, int Hq, int Hkv, int D, int dtype, d
             for (int d = 0; d < D; ++d) o[d] = 0.0;
             for (int j = 0; j < S; ++j) {
                 const double p = s[j] / z;
-                if (j < L) {
-                    const size_t vo = ((size_t)j * Hkv + kh) * D;
-                    for (int d = 0; d < D; ++d) o[d] += p * widen(prefix_v, dtype, vo + d);
-                } else {
-                    const size_t vo = (((size_t)n * B + (j - L)) * Hkv + kh) * D;
-                    for (int d = 0; d < D; ++d) o[d] += p * widen(block_v, dtype, vo + d);
-                }
+                const void *arr; size_t vo;
+                FDDO_KEY(j, prefix_v, ext_v, block_v, arr, vo);
+                for (int d = 0; d < D; ++d) o[d] += p * widen(arr, dtype, vo + d);
             }
+            #undef FDDO_KEY
         }
         free(s);
     }
     return bad;
+}
+
+/* ext[n, E .. E+B-1] = block[n] for K and V: the finished block joins the rollout's private extension. */
+int fddo_block_commit(int N, int B, int E, int Ecap, int Hkv, int D, int dtype,
+                      const void *block_k, const void *block_v, void *ext_k, void *ext_v)
+{
+    if (N <= 0 || B <= 0 || E < 0 || E + B > Ecap || Hkv <= 0 || D <= 0) return 1;
+    const size_t row = (size_t)Hkv * D * elem_size(dtype);
+    for (int n = 0; n < N; ++n) {
+        memcpy((char *)ext_k + ((size_t)n * Ecap + E) * row, (const char *)block_k + (size_t)n * B * row, (size_t)B * row);
+        memcpy((char *)ext_v + ((size_t)n * Ecap + E) * row, (const char *)block_v + (size_t)n * B * row, (size_t)B * row);
+    }
+    return 0;
 }
 
 /*
