@@ -206,6 +206,42 @@ def time_spec_verify(F, w, d, g, logits, steps, warmup):
     }
 
 
+def time_extension(F, w, d, g, steps, warmup):
+    """Third block of the trajectory section: every rollout has committed two
+    blocks of its own since the fork (E = 2B extension rows), plus the commit."""
+    import torch
+    st = {k: dev(d[k]) for k in ("block_k", "block_v")}
+    E = 2 * w.B
+    rng = np.random.default_rng([w.seed, 78])
+    import fdd_workloads as W
+    ext = [dev(W.to_storage(rng.standard_normal((w.N, 3 * w.B, w.Hkv, w.D)).astype(np.float32), w.dtype)) for _ in range(2)]
+    out = torch.empty_like(g["q"])
+    packed_v = F.fdd_prefix_pack(g["prefix_v"])
+    ws = torch.empty(max(256, F.fdd_block_attn_workspace(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"],
+                                                         prefix_v_packed=packed_v)), dtype=torch.uint8, device="cuda")
+    ev = Events(steps)
+    for i in range(warmup + steps):
+        if i >= warmup:
+            F.fdd_profile_attn_events(*ev.pairs[i - warmup])
+        F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"], out=out, workspace=ws,
+                         prefix_v_packed=packed_v, ext_k=ext[0], ext_v=ext[1], E=E)
+    torch.cuda.synchronize()
+    F.fdd_profile_attn_events(None, None)
+    attn_ms = ev.mean_ms(steps)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for i in range(20):
+        F.fdd_block_commit(st["block_k"], st["block_v"], ext[0], ext[1], E)
+    c1.record()
+    torch.cuda.synchronize()
+    flops = 4.0 * w.N * w.B * w.Hq * (w.L + E + w.B) * w.D
+    return {"workload": f"{w.name} with E={E} private extension rows per rollout",
+            "attn_kernel_us": round(attn_ms * 1e3, 2), "attn_tflops": round(flops / (attn_ms * 1e-3) / 1e12, 1),
+            "attn_frac_peak_mfma": round(flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "commit_call_us": round(c0.elapsed_time(c1) / 20 * 1e3, 2),
+            "commit_bytes": 4 * w.N * w.B * w.Hkv * w.D * 2}
+
+
 def cpu_baseline(w, d, logits):
     """The fp64 oracle as it stands on a bounded sample of one step."""
     import oracle
@@ -365,6 +401,7 @@ def main():
         res["n1_prefix_stream_L16384"] = time_attention_only(F, n1_long, 200, 20, 20)
         if has_unmask:
             res["spec_verify"] = time_spec_verify(F, w, d, g, logits, 100, 10)
+        res["extension_block"] = time_extension(F, w, d, g, 50, 5)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, logits_h)
     print(json.dumps(res))

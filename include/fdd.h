@@ -100,6 +100,15 @@ typedef struct fdd_attn_params {
     int32_t splits;                /* 0 = automatic */
     int32_t flags;                 /* FDD_ATTN_* bits; unknown bits are rejected */
     const void *prefix_v_packed;   /* optional: output of fdd_prefix_pack for this prefix_v, or NULL */
+    /* Per-rollout extension: the blocks rollout n has finished since the fork ("Shared prefix": the
+     * trajectory section is continued N times and spans several blocks; "Block-Causal Diffusion": a block
+     * attends causally to all earlier blocks).  Rows ext[n, 0..E) are keys of rollout n only, between
+     * the shared prefix and the live block; they are fully visible, also with FDD_ATTN_CAUSAL_BLOCK.
+     * E = 0 (pointers may then be NULL) is the plain two-run form. */
+    const void *ext_k;             /* [N, ext_capacity, Hkv, D] */
+    const void *ext_v;             /* [N, ext_capacity, Hkv, D] */
+    int32_t E;                     /* valid extension rows per rollout, 0 <= E <= ext_capacity */
+    int32_t ext_capacity;          /* rows allocated per rollout */
 } fdd_attn_params;
 
 /* Bytes of scratch fdd_block_attn needs for these params (host-only
@@ -236,6 +245,25 @@ fdd_status fdd_verify_step(const fdd_verify_params *p);
  * bytes must be a multiple of 4; src and dst must not overlap.
  */
 fdd_status fdd_fork_block(int32_t N, size_t bytes, const void *src, void *dst, void *stream);
+
+/* fdd_block_commit: a finished block joins its rollout's extension,
+ * ext_k[n, E..E+B) = block_k[n], ext_v likewise; the caller then passes E + B as
+ * the extension length of the next block's attention calls.  E + B must not
+ * exceed ext_capacity; pointers 16-byte aligned; the arrays must not overlap. */
+typedef struct fdd_commit_params {
+    int32_t N, B, Hkv, D;
+    int32_t dtype;
+    int32_t E;                     /* rows already in the extension */
+    int32_t ext_capacity;
+    int32_t reserved;              /* must be 0 */
+    const void *block_k;           /* [N,B,Hkv,D] */
+    const void *block_v;
+    void *ext_k;                   /* [N,ext_capacity,Hkv,D] in/out */
+    void *ext_v;
+    void *stream;
+} fdd_commit_params;
+
+fdd_status fdd_block_commit(const fdd_commit_params *p);
 
 /* fdd_block_kv_update: refresh the K/V rows of positions committed by the
  * last unmask step.  No model is inside this library, so the new row of a

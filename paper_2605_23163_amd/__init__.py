@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     FddError,
     fdd_block_attn,
     fdd_block_attn_workspace,
+    fdd_block_commit,
     fdd_block_kv_update,
     fdd_fork_block,
     fdd_last_error,

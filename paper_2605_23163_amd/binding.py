@@ -17,7 +17,7 @@ FDD_F32, FDD_BF16 = 0, 1
 FDD_ATTN_CAUSAL_BLOCK = 1
 EXPORTS = ("fdd_block_attn_workspace", "fdd_block_attn", "fdd_prefix_pack_bytes", "fdd_prefix_pack",
            "fdd_unmask_workspace", "fdd_unmask_step", "fdd_verify_workspace", "fdd_verify_step",
-           "fdd_fork_block", "fdd_block_kv_update", "fdd_profile_attn_events", "fdd_last_error", "fdd_version")
+           "fdd_fork_block", "fdd_block_kv_update", "fdd_block_commit", "fdd_profile_attn_events", "fdd_last_error", "fdd_version")
 
 
 class FddError(RuntimeError):
@@ -33,7 +33,8 @@ class AttnParams(C.Structure):
                 ("block_k", C.c_void_p), ("block_v", C.c_void_p), ("scaffold_mask", C.c_void_p),
                 ("out", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
                 ("stream", C.c_void_p), ("splits", C.c_int32), ("flags", C.c_int32),
-                ("prefix_v_packed", C.c_void_p)]
+                ("prefix_v_packed", C.c_void_p), ("ext_k", C.c_void_p), ("ext_v", C.c_void_p),
+                ("E", C.c_int32), ("ext_capacity", C.c_int32)]
 
 
 class UnmaskParams(C.Structure):
@@ -57,6 +58,13 @@ class KvUpdateParams(C.Structure):
                 ("dtype", C.c_int32), ("tokens", C.c_void_p), ("committed", C.c_void_p),
                 ("table_k", C.c_void_p), ("table_v", C.c_void_p), ("block_k", C.c_void_p),
                 ("block_v", C.c_void_p), ("stream", C.c_void_p)]
+
+
+class CommitParams(C.Structure):
+    _fields_ = [("N", C.c_int32), ("B", C.c_int32), ("Hkv", C.c_int32), ("D", C.c_int32), ("dtype", C.c_int32),
+                ("E", C.c_int32), ("ext_capacity", C.c_int32), ("reserved", C.c_int32),
+                ("block_k", C.c_void_p), ("block_v", C.c_void_p), ("ext_k", C.c_void_p), ("ext_v", C.c_void_p),
+                ("stream", C.c_void_p)]
 
 
 def library_path() -> str:
@@ -94,6 +102,8 @@ def load_library():
         lib.fdd_fork_block.argtypes = [C.c_int32, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.fdd_block_kv_update.restype = C.c_int
         lib.fdd_block_kv_update.argtypes = [C.POINTER(KvUpdateParams)]
+        lib.fdd_block_commit.restype = C.c_int
+        lib.fdd_block_commit.argtypes = [C.POINTER(CommitParams)]
         lib.fdd_profile_attn_events.restype = C.c_int
         lib.fdd_profile_attn_events.argtypes = [C.c_void_p, C.c_void_p]
         lib.fdd_last_error.restype = C.c_char_p
@@ -159,7 +169,7 @@ def _workspace(ws, need, device):
 
 
 def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed=None,
-                 causal_block=False):
+                 causal_block=False, ext_k=None, ext_v=None, E=0):
     N, B, Hq, D = q.shape
     L, Hkv = prefix_k.shape[0], block_k.shape[2]
     if tuple(prefix_k.shape[1:]) != (Hkv, D) or tuple(prefix_v.shape) != tuple(prefix_k.shape):
@@ -182,6 +192,13 @@ def _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, sc
     p.splits = int(splits)
     p.prefix_v_packed = _dev(prefix_v_packed, "prefix_v_packed")
     p.flags = FDD_ATTN_CAUSAL_BLOCK if causal_block else 0
+    p.E = int(E)
+    if ext_k is not None:
+        if tuple(ext_k.shape) != tuple(ext_v.shape) or ext_k.shape[0] != N or tuple(ext_k.shape[2:]) != (Hkv, D):
+            raise ValueError("ext_k / ext_v must be [N,ext_capacity,Hkv,D]")
+        if ext_k.dtype != q.dtype or ext_v.dtype != q.dtype:
+            raise TypeError("q, k and v must share one element type")
+        p.ext_k, p.ext_v, p.ext_capacity = _dev(ext_k, "ext_k"), _dev(ext_v, "ext_v"), ext_k.shape[1]
     return p
 
 
@@ -207,20 +224,24 @@ def fdd_prefix_pack(prefix_v, packed=None, stream=None):
 
 
 def fdd_block_attn_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0, prefix_v_packed=None) -> int:
+    # (the per-rollout extension does not change the workspace size)
     p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, None, None, None, splits, prefix_v_packed)
     return load_library().fdd_block_attn_workspace(C.byref(p))
 
 
 def fdd_block_attn(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask=None, out=None, scale=None,
-                   workspace=None, stream=None, splits=0, prefix_v_packed=None, causal_block=False):
+                   workspace=None, stream=None, splits=0, prefix_v_packed=None, causal_block=False,
+                   ext_k=None, ext_v=None, E=0):
     """out[N,B,Hq,D] = shared-prefix block-causal attention (see include/fdd.h).
-    ``causal_block=True`` is the verify pass: causal inside the block."""
+    ``causal_block=True`` is the verify pass: causal inside the block.
+    ``ext_k/ext_v`` [N,ext_capacity,Hkv,D] with ``E`` valid rows: the blocks each
+    rollout has committed since the fork."""
     import torch
     lib = load_library()
     if out is None:
         out = torch.empty_like(q)
     p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed,
-                     causal_block)
+                     causal_block, ext_k, ext_v, E)
     need = lib.fdd_block_attn_workspace(C.byref(p))
     ws, nbytes = _workspace(workspace, need, q.device)
     p.workspace = ws.data_ptr() if ws is not None else None
@@ -336,3 +357,16 @@ def fdd_block_kv_update(tokens, committed, table_k, table_v, block_k, block_v, s
     p.stream = _stream_ptr(stream)
     _check(lib.fdd_block_kv_update(C.byref(p)))
     return block_k, block_v
+
+
+def fdd_block_commit(block_k, block_v, ext_k, ext_v, E, stream=None):
+    """ext[n, E:E+B] = block[n] for K and V (in place); returns E + B."""
+    lib = load_library()
+    N, B, Hkv, D = block_k.shape
+    p = CommitParams()
+    p.N, p.B, p.Hkv, p.D, p.dtype, p.E, p.ext_capacity = N, B, Hkv, D, _dtype_code(block_k), int(E), ext_k.shape[1]
+    p.block_k, p.block_v = _dev(block_k, "block_k"), _dev(block_v, "block_v")
+    p.ext_k, p.ext_v = _dev(ext_k, "ext_k"), _dev(ext_v, "ext_v")
+    p.stream = _stream_ptr(stream)
+    _check(lib.fdd_block_commit(C.byref(p)))
+    return int(E) + B

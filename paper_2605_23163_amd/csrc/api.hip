@@ -47,6 +47,10 @@ fdd_status check_attn_shape(const fdd_attn_params* p)
         if (p->Hkv * mt * tpu >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq*L too large");
     }
     if (std::isnan(p->scale) || std::isinf(p->scale)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: scale is not finite");
+    if (p->E < 0 || p->ext_capacity < 0 || p->E > p->ext_capacity)
+        return fail(FDD_ERR_SHAPE, "fdd_block_attn: need 0 <= E <= ext_capacity (got E=%d, ext_capacity=%d)", p->E, p->ext_capacity);
+    if ((long long)p->N * p->ext_capacity * p->Hkv * p->D * 4 >= (1ll << 32))
+        return fail(FDD_ERR_SHAPE, "fdd_block_attn: extension K (N*ext_capacity*Hkv*D elements) must stay below 4 GiB");
     return FDD_OK;
 }
 
@@ -152,7 +156,9 @@ fdd_status fdd_block_attn(const fdd_attn_params* p)
     if (st != FDD_OK) return st;
     if (!p->q || !p->block_k || !p->block_v || !p->out) return fail(FDD_ERR_NULL, "fdd_block_attn: q, block_k, block_v and out must not be NULL");
     if (p->L > 0 && (!p->prefix_k || !p->prefix_v)) return fail(FDD_ERR_NULL, "fdd_block_attn: prefix_k / prefix_v is NULL with L=%d", p->L);
-    const void* ptrs[] = {p->q, p->prefix_k, p->prefix_v, p->block_k, p->block_v, p->out, p->prefix_v_packed};
+    if (p->E > 0 && (!p->ext_k || !p->ext_v)) return fail(FDD_ERR_NULL, "fdd_block_attn: ext_k / ext_v is NULL with E=%d", p->E);
+    const void* ptrs[] = {p->q, p->prefix_k, p->prefix_v, p->block_k, p->block_v, p->out, p->prefix_v_packed,
+                          p->E > 0 ? p->ext_k : nullptr, p->E > 0 ? p->ext_v : nullptr};
     for (const void* x : ptrs)
         if (x && !aligned16(x)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: data pointers must be 16-byte aligned");
     if (p->out == p->q) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: out must not alias q");
@@ -284,6 +290,26 @@ fdd_status fdd_fork_block(int32_t N, size_t bytes, const void* src, void* dst, v
     if (s0 < d0 + (size_t)N * bytes && d0 < s0 + bytes) return fail(FDD_ERR_UNSUPPORTED, "fdd_fork_block: src and dst overlap");
     hipError_t e = launch_fork_block(N, bytes, src, dst, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_fork_block: launch failed: %s", hipGetErrorString(e));
+    return FDD_OK;
+}
+
+fdd_status fdd_block_commit(const fdd_commit_params* p)
+{
+    if (!p) return fail(FDD_ERR_NULL, "fdd_block_commit: params is NULL");
+    if (p->N <= 0 || p->B <= 0 || p->Hkv <= 0 || p->D <= 0 || p->E < 0 || p->ext_capacity <= 0)
+        return fail(FDD_ERR_SHAPE, "fdd_block_commit: N, B, Hkv, D, ext_capacity must be positive and E >= 0");
+    if ((long long)p->E + p->B > p->ext_capacity)
+        return fail(FDD_ERR_SHAPE, "fdd_block_commit: E + B = %lld exceeds ext_capacity = %d", (long long)p->E + p->B, p->ext_capacity);
+    if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_block_commit: dtype %d is neither FDD_F32 nor FDD_BF16", p->dtype);
+    if (p->reserved != 0) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_commit: reserved field must be 0");
+    if (!p->block_k || !p->block_v || !p->ext_k || !p->ext_v) return fail(FDD_ERR_NULL, "fdd_block_commit: block_k, block_v, ext_k and ext_v must not be NULL");
+    const size_t es = p->dtype == FDD_BF16 ? 2 : 4;
+    if (((size_t)p->Hkv * p->D * es) % 16) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_commit: a K/V row must be a multiple of 16 bytes");
+    const void* ptrs[] = {p->block_k, p->block_v, p->ext_k, p->ext_v};
+    for (const void* x : ptrs)
+        if (!aligned16(x)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_commit: pointers must be 16-byte aligned");
+    hipError_t e = launch_block_commit(*p, static_cast<hipStream_t>(p->stream));
+    if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_commit: launch failed: %s", hipGetErrorString(e));
     return FDD_OK;
 }
 

@@ -88,6 +88,9 @@ struct Args {
     float* ws_o;
     float* ws_ml;
     const uint16_t* vt;   // packed V^T tiles of the full prefix tiles (PACKED kernels only)
+    const uint16_t* ek;   // per-rollout extension [N, Ecap, Hkv, D]
+    const uint16_t* ev;
+    int E, Ecap;
     int N, B, L, Hq, Hkv, G, R, MT, TP;
     int TPF;        // full prefix tiles = L / 64
     int TPU;        // units per M-tile = max(TP, 1)
@@ -337,34 +340,46 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const bool wave_has_rows = row0 < a.R;
         const int wg_n_lo = __builtin_amdgcn_readfirstlane(row0_wg / BG);
         const int wg_n_hi = __builtin_amdgcn_readfirstlane((min(row0_wg + MROWS - 1, a.R - 1)) / BG);
-        const int ttpr = (a.B + KT - 1) / KT;            // tail tiles per rollout
+        const int tte = (a.E + KT - 1) / KT;             // tiles of a rollout's extension
+        const int ttpr = tte + (a.B + KT - 1) / KT;      // private tiles per rollout: extension, then block
         const int n_tail = (t_end == a.TPU) ? (wg_n_hi - wg_n_lo + 1) * ttpr : 0;
         const int n_tiles = n_prefix + n_tail;
 
         struct Tile {
-            int row_base;   // first key, as a row of prefix K/V or of block K/V
+            int src;        // 0: shared prefix, 1: a rollout's extension, 2: a rollout's block
+            int row_base;   // first key, as a row of that K/V array
             int valid;      // keys that exist
             int rollout;    // whose rows may see it (-1: every row)
-            int key0;       // block position of the first key (tail tiles)
+            int key0;       // block position of the first key (block tiles)
         };
         auto tile_at = [&](int j) -> Tile {
             Tile t;
             if (j < n_prefix) {
+                t.src = 0;
                 t.row_base = (t0 + j) * KT;
                 t.valid = min(KT, a.L - t.row_base);
                 t.rollout = -1;
                 t.key0 = 0;
             } else {
                 const int jj = j - n_prefix;
-                int n = wg_n_lo + jj, k0 = 0;
+                int n = wg_n_lo + jj, w = 0;
                 if (ttpr > 1) {
                     n = wg_n_lo + jj / ttpr;
-                    k0 = (jj % ttpr) * KT;
+                    w = jj % ttpr;
                 }
-                t.row_base = n * a.B + k0;
-                t.valid = min(KT, a.B - k0);
                 t.rollout = n;
-                t.key0 = k0;
+                if (w < tte) {
+                    t.src = 1;
+                    t.row_base = n * a.Ecap + w * KT;
+                    t.valid = min(KT, a.E - w * KT);
+                    t.key0 = 0;
+                } else {
+                    const int k0 = (w - tte) * KT;
+                    t.src = 2;
+                    t.row_base = n * a.B + k0;
+                    t.valid = min(KT, a.B - k0);
+                    t.key0 = k0;
+                }
             }
             return t;
         };
@@ -373,12 +388,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         // their scores are masked), so nothing is read out of bounds
         auto fetch_masked = [&](int j) {
             const Tile t = tile_at(j);
-            const bool pre = j < n_prefix;
-            const uint32_t bytes = pre ? (uint32_t)a.L * stride2 : (uint32_t)(a.N * a.B) * stride2;
-            const __amdgpu_buffer_rsrc_t k_rsrc =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(pre ? a.pk : a.bk), 0, bytes, RSRC_FLAGS);
-            const __amdgpu_buffer_rsrc_t v_rsrc =
-                __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(pre ? a.pv : a.bv), 0, bytes, RSRC_FLAGS);
+            const uint32_t rows_in_array = t.src == 0 ? (uint32_t)a.L : t.src == 1 ? (uint32_t)(a.N * a.Ecap) : (uint32_t)(a.N * a.B);
+            const uint32_t bytes = rows_in_array * stride2;
+            const uint16_t* const ksrc = t.src == 0 ? a.pk : t.src == 1 ? a.ek : a.bk;
+            const uint16_t* const vsrc = t.src == 0 ? a.pv : t.src == 1 ? a.ev : a.bv;
+            const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(ksrc), 0, bytes, RSRC_FLAGS);
+            const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(vsrc), 0, bytes, RSRC_FLAGS);
             const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)t.row_base * stride2 + (uint32_t)(kh * D * 2));
             const uint32_t slot = (uint32_t)(j & (NB - 1)) * C::T_BYTES;
             const int last = t.valid - 1;
@@ -624,7 +639,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int key = kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                        const bool later = a.causal && t.rollout >= 0 && t.key0 + key > my_b;   // verify pass: causal inside the block
+                        const bool later = a.causal && t.src == 2 && t.key0 + key > my_b;   // verify pass: causal inside the block
                         if (!row_sees || key >= t.valid || later) s[kb][v] = -INFINITY;
                         mx = fmaxf(mx, s[kb][v]);
                     }
@@ -784,6 +799,9 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     const bool pack_now = plan.packed && !p.prefix_v_packed;
     a.vt = pack_now ? reinterpret_cast<const uint16_t*>(ws + plan.ws_o_bytes + plan.ws_ml_bytes)
                     : static_cast<const uint16_t*>(p.prefix_v_packed);
+    a.ek = static_cast<const uint16_t*>(p.ext_k);
+    a.ev = static_cast<const uint16_t*>(p.ext_v);
+    a.E = p.E; a.Ecap = p.ext_capacity;
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.TPF = p.L / 64;
     a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.S = plan.uniform;

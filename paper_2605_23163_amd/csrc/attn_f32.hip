@@ -25,6 +25,9 @@ struct Args {
     float* out;
     float* ws_o;
     float* ws_ml;
+    const float* ek;   // per-rollout extension [N, Ecap, Hkv, D]
+    const float* ev;
+    int E, Ecap;
     int N, B, L, Hq, Hkv, G, R, MT, TP, S;
     int causal;   // in-block keys are visible up to the query's own position only
     float c;   // scale * log2(e)
@@ -73,7 +76,8 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
     const int t0 = (int)(((long long)split * a.TP) / a.S);
     const int t1 = (int)(((long long)(split + 1) * a.TP) / a.S);
     const int n_prefix = t1 - t0;
-    const int tail_per = (a.B + KT - 1) / KT;
+    const int ext_per = (a.E + KT - 1) / KT;                  // tiles of a rollout's extension
+    const int tail_per = ext_per + (a.B + KT - 1) / KT;       // private tiles per rollout: extension, then block
     const int n_tail = (split == a.S - 1) ? (wg_n_hi - wg_n_lo + 1) * tail_per : 0;
     const size_t kv_stride = (size_t)a.Hkv * D;
 
@@ -85,6 +89,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
     for (int i = 0; i < n_prefix + n_tail; ++i) {
         const float *kp, *vp;
         int valid, rollout, blk0 = 0;
+        bool in_block = false;
         if (i < n_prefix) {
             const int key0 = (t0 + i) * KT;
             kp = a.pk + (size_t)key0 * kv_stride + (size_t)kh * D;
@@ -94,13 +99,23 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
         } else {
             const int j = i - n_prefix;
             const int n = wg_n_lo + j / tail_per;
-            const int key0 = (j % tail_per) * KT;
-            const size_t off = ((size_t)n * a.B + key0) * kv_stride + (size_t)kh * D;
-            kp = a.bk + off;
-            vp = a.bv + off;
-            valid = min(KT, a.B - key0);
+            const int w = j % tail_per;
             rollout = n;
-            blk0 = key0;
+            if (w < ext_per) {
+                const int key0 = w * KT;
+                const size_t off = ((size_t)n * a.Ecap + key0) * kv_stride + (size_t)kh * D;
+                kp = a.ek + off;
+                vp = a.ev + off;
+                valid = min(KT, a.E - key0);
+            } else {
+                const int key0 = (w - ext_per) * KT;
+                const size_t off = ((size_t)n * a.B + key0) * kv_stride + (size_t)kh * D;
+                kp = a.bk + off;
+                vp = a.bv + off;
+                valid = min(KT, a.B - key0);
+                blk0 = key0;
+                in_block = true;
+            }
         }
         __syncthreads();   // previous tile fully consumed (and qs written, first time)
         for (int x = tid; x < KT * (D / 4); x += THREADS) {
@@ -132,7 +147,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
                 acc = fmaf(qq.z, kk.z, acc);
                 acc = fmaf(qq.w, kk.w, acc);
             }
-            const bool later = a.causal && rollout >= 0 && blk0 + key > my_b;
+            const bool later = a.causal && in_block && blk0 + key > my_b;
             sc[j] = (sees && key < valid && !later) ? acc : -INFINITY;
             mx = fmaxf(mx, sc[j]);
         }
@@ -312,6 +327,9 @@ hipError_t launch_attn_f32(const fdd_attn_params& p, const AttnPlan& plan, float
     a.out = static_cast<float*>(p.out);
     a.ws_o = static_cast<float*>(p.workspace);
     a.ws_ml = reinterpret_cast<float*>(static_cast<char*>(p.workspace) + plan.ws_o_bytes);
+    a.ek = static_cast<const float*>(p.ext_k);
+    a.ev = static_cast<const float*>(p.ext_v);
+    a.E = p.E; a.Ecap = p.ext_capacity;
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.S = plan.splits;
     a.c = scale * 1.4426950408889634f;

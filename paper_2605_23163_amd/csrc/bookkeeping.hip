@@ -4,7 +4,9 @@
 // pointer and never copied, so a fork only replicates the block-sized private
 // arrays (block K/V, tokens, mask).  After an unmask step the K/V rows of the
 // newly committed positions are refreshed; with no model in scope the new row
-// is looked up in caller-provided tables by token id.
+// is looked up in caller-provided tables by token id.  A finished block is
+// appended to its rollout's private extension (the blocks decoded since the
+// fork), which later blocks of that rollout attend to.
 #include "fdd_internal.h"
 
 namespace fdd {
@@ -46,7 +48,32 @@ __global__ __launch_bounds__(256) void kv_update_kernel(int T, int row_vecs, con
     }
 }
 
+// grid (N, chunks): rollout n's block (`block_vecs` 16-byte pieces) is copied to piece offset
+// `dst0` of its extension (`ext_vecs` pieces per rollout), K and V alike
+__global__ __launch_bounds__(256) void commit_kernel(size_t block_vecs, size_t ext_vecs, size_t dst0, const u32x4* bk,
+                                                      const u32x4* bv, u32x4* ek, u32x4* ev)
+{
+    const size_t n = blockIdx.x;
+    for (size_t c = (size_t)blockIdx.y * blockDim.x + threadIdx.x; c < block_vecs; c += (size_t)gridDim.y * blockDim.x) {
+        ek[n * ext_vecs + dst0 + c] = bk[n * block_vecs + c];
+        ev[n * ext_vecs + dst0 + c] = bv[n * block_vecs + c];
+    }
+}
+
 }  // namespace
+
+hipError_t launch_block_commit(const fdd_commit_params& p, hipStream_t s)
+{
+    const size_t es = p.dtype == FDD_BF16 ? 2 : 4;
+    const size_t row_vecs = (size_t)p.Hkv * p.D * es / 16;
+    const size_t block_vecs = row_vecs * p.B;
+    unsigned chunks = (unsigned)((block_vecs + 255) / 256);
+    if (chunks > 64) chunks = 64;
+    hipLaunchKernelGGL(commit_kernel, dim3((unsigned)p.N, chunks), dim3(256), 0, s, block_vecs, row_vecs * p.ext_capacity,
+                       row_vecs * p.E, static_cast<const u32x4*>(p.block_k), static_cast<const u32x4*>(p.block_v),
+                       static_cast<u32x4*>(p.ext_k), static_cast<u32x4*>(p.ext_v));
+    return hipGetLastError();
+}
 
 hipError_t launch_fork_block(int N, size_t bytes, const void* src, void* dst, hipStream_t s)
 {

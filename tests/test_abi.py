@@ -143,6 +143,32 @@ def test_bookkeeping_errors(lib):
     assert lib.fdd_block_kv_update(None) == 1
 
 
+def test_extension_and_commit_errors(lib):
+    # attention with a per-rollout extension: every host-detectable mistake is a status code
+    for kw, code in [(dict(E=-1), 2), (dict(E=8, ext_capacity=4, ext_k=2048, ext_v=2304), 2),
+                     (dict(E=8, ext_capacity=8), 1), (dict(E=8, ext_capacity=8, ext_k=2048, ext_v=2056), 4),
+                     (dict(E=8, ext_capacity=1 << 30, ext_k=2048, ext_v=2304), 2)]:
+        assert lib.fdd_block_attn(C.byref(attn(**kw))) == code, kw
+        assert lib.fdd_last_error().decode().startswith("fdd_block_attn:")
+    # E = 0 ignores the extension pointers; the workspace does not depend on E
+    assert lib.fdd_block_attn_workspace(C.byref(attn(E=64, ext_capacity=64, ext_k=2048, ext_v=2304))) == \
+        lib.fdd_block_attn_workspace(C.byref(attn()))
+
+    def cp(**kw):
+        p = bd.CommitParams()
+        base = dict(N=4, B=32, Hkv=4, D=128, dtype=bd.FDD_BF16, E=32, ext_capacity=96, block_k=256, block_v=512,
+                    ext_k=1024, ext_v=2048)
+        base.update(kw)
+        for k, v in base.items():
+            setattr(p, k, v)
+        return p
+    for kw, code in [(dict(N=0), 2), (dict(E=65), 2), (dict(E=-1), 2), (dict(dtype=7), 3), (dict(reserved=1), 4),
+                     (dict(ext_k=None), 1), (dict(block_v=None), 1), (dict(ext_v=2056), 4), (dict(Hkv=1, D=4, dtype=bd.FDD_BF16), 4)]:
+        assert lib.fdd_block_commit(C.byref(cp(**kw))) == code, kw
+        assert lib.fdd_last_error().decode().startswith("fdd_block_commit:")
+    assert lib.fdd_block_commit(None) == 1
+
+
 def test_binding_refuses_host_tensors():
     import torch
     q = torch.zeros(1, 8, 4, 64)

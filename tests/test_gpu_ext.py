@@ -1,0 +1,119 @@
+"""GPU parity of the per-rollout extension (blocks committed since the fork) and
+of fdd_block_commit against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import fdd_workloads as W
+from tests.gpu_util import print_case, rand_attn, to_dev, to_f64
+
+pytestmark = pytest.mark.gpu
+
+TOL = {W.BF16: 2e-2, W.F32: 1e-4}
+
+
+@pytest.fixture(scope="module")
+def F():
+    import paper_2605_23163_amd as F
+    F.load_library()
+    return F
+
+
+def rand_ext(rng, N, Ecap, Hkv, D, dtype):
+    return (W.to_storage(rng.standard_normal((N, Ecap, Hkv, D)).astype(np.float32), dtype),
+            W.to_storage(rng.standard_normal((N, Ecap, Hkv, D)).astype(np.float32), dtype))
+
+
+# (N, B, L, Hq, Hkv, D, E, Ecap)
+SHAPES = [(1, 8, 256, 4, 1, 64, 8, 8), (3, 20, 333, 14, 2, 128, 37, 40), (2, 32, 64, 8, 8, 64, 64, 96),
+          (4, 16, 0, 4, 2, 128, 100, 128), (9, 32, 1000, 28, 4, 128, 64, 64), (5, 70, 200, 7, 1, 128, 130, 140),
+          (16, 32, 4096, 28, 4, 128, 32, 64)]
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", [W.BF16, W.F32])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_extension_matches_oracle(F, oracle, shape, dtype, causal):
+    N, B, L, Hq, Hkv, D, E, Ecap = shape
+    if dtype == W.F32 and N * B * Hq * (L + E + B) > 3e7:
+        pytest.skip("fp32 path is for small exactness checks")
+    print_case(test="ext_attn", shape=shape, dtype=dtype, causal=causal)
+    rng = np.random.default_rng(hash(shape) % 2**32 + 3)
+    d = rand_attn(rng, N, B, L, Hq, Hkv, D, dtype)
+    ek, ev = rand_ext(rng, N, Ecap, Hkv, D, dtype)
+    t = {k: to_dev(v) for k, v in d.items()}
+    tek, tev = to_dev(ek), to_dev(ev)
+    if Ecap > E:      # rows beyond E must not be read into the result
+        junk = torch.full_like(tek[:, E:], float("nan"))
+        tek[:, E:] = junk
+        tev[:, E:] = junk
+    out = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"], causal_block=causal,
+                           ext_k=tek, ext_v=tev, E=E)
+    torch.cuda.synchronize()
+    rows = None
+    if N * B * Hq > 4096:
+        pick = rng.choice(N * B * Hq, 4096, replace=False)
+        rows = np.stack([pick // (B * Hq), (pick // Hq) % B, pick % Hq], 1).astype(np.int32)
+    ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"], causal_block=causal,
+                            ext_k=ek, ext_v=ev, E=E, rows=rows)
+    got = to_f64(out)
+    if rows is not None:
+        got = got[rows[:, 0], rows[:, 1], rows[:, 2]]
+    err = np.abs(got - ref).max()
+    assert err <= TOL[dtype], f"max-abs error {err}"
+    # E = 0 with the same pointers is the plain two-run form
+    plain = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"], causal_block=causal)
+    e0 = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"], causal_block=causal,
+                          ext_k=tek, ext_v=tev, E=0)
+    assert torch.equal(plain, e0) and not torch.equal(plain, out)
+
+
+@pytest.mark.parametrize("dtype", [W.BF16, W.F32])
+def test_block_commit_is_bit_exact(F, oracle, dtype):
+    print_case(test="block_commit", dtype=dtype)
+    rng = np.random.default_rng(8)
+    N, B, Hkv, D, Ecap = 5, 32, 4, 128, 100
+    bk, bv = rand_ext(rng, N, B, Hkv, D, dtype)
+    ek, ev = rand_ext(rng, N, Ecap, Hkv, D, dtype)
+    for E in (0, 32, 68):
+        tek, tev = to_dev(ek), to_dev(ev)
+        assert F.fdd_block_commit(to_dev(bk), to_dev(bv), tek, tev, E) == E + B
+        torch.cuda.synchronize()
+        rk, rv = oracle.block_commit(bk, bv, ek, ev, E)
+        view = (lambda x: x.view(torch.int16).cpu().numpy().view(np.uint16)) if dtype == W.BF16 else (lambda x: x.cpu().numpy())
+        assert np.array_equal(view(tek), rk) and np.array_equal(view(tev), rv)
+    with pytest.raises(F.FddError):
+        F.fdd_block_commit(to_dev(bk), to_dev(bv), to_dev(ek), to_dev(ev), 69)
+
+
+def test_three_block_lifecycle_after_a_fork(F, oracle):
+    # fork, then three blocks per rollout: attend, commit, attend with a longer extension.
+    # Every block's output must match the oracle given the same extension, and the extension
+    # built on the GPU must equal the one the oracle builds.
+    print_case(test="ext_lifecycle")
+    rng = np.random.default_rng(12)
+    N, B, L, Hq, Hkv, D = 6, 32, 2048, 28, 4, 128
+    pre = rand_attn(rng, N, B, L, Hq, Hkv, D, W.BF16)
+    pk, pv = to_dev(pre["prefix_k"]), to_dev(pre["prefix_v"])
+    packed = F.fdd_prefix_pack(pv)
+    ek_h = np.zeros((N, 2 * B, Hkv, D), dtype=np.uint16)
+    ev_h = np.zeros((N, 2 * B, Hkv, D), dtype=np.uint16)
+    ek, ev = to_dev(ek_h), to_dev(ev_h)
+    E = 0
+    for blk in range(3):
+        d = rand_attn(rng, N, B, L, Hq, Hkv, D, W.BF16)
+        q, bk, bv = to_dev(d["q"]), to_dev(d["block_k"]), to_dev(d["block_v"])
+        out = F.fdd_block_attn(q, pk, pv, bk, bv, prefix_v_packed=packed, ext_k=ek, ext_v=ev, E=E)
+        torch.cuda.synchronize()
+        pick = rng.choice(N * B * Hq, 1500, replace=False)
+        rows = np.stack([pick // (B * Hq), (pick // Hq) % B, pick % Hq], 1).astype(np.int32)
+        ref = oracle.block_attn(d["q"], pre["prefix_k"], pre["prefix_v"], d["block_k"], d["block_v"],
+                                ext_k=ek_h, ext_v=ev_h, E=E, rows=rows)
+        err = np.abs(to_f64(out)[rows[:, 0], rows[:, 1], rows[:, 2]] - ref).max()
+        assert err <= 2e-2, f"block {blk}: max-abs error {err}"
+        if blk < 2:
+            ek_h, ev_h = oracle.block_commit(d["block_k"], d["block_v"], ek_h, ev_h, E)
+            E = F.fdd_block_commit(bk, bv, ek, ev, E)
+            torch.cuda.synchronize()
+            assert np.array_equal(ek.view(torch.int16).cpu().numpy().view(np.uint16), ek_h)
+    assert E == 2 * B
