@@ -44,6 +44,8 @@ def _load():
         lib.fddo_block_attn_ext.restype = c.c_int
         lib.fddo_block_attn_ext.argtypes = ([c.c_int] * 9 + [c.c_double, c.c_int] + [c.c_void_p] * 8 +
                                             [c.c_int64, c.c_void_p])
+        lib.fddo_traj_mean.restype = c.c_int
+        lib.fddo_traj_mean.argtypes = [c.c_int, c.c_int, c.c_int, c.c_void_p, c.c_void_p]
         lib.fddo_block_commit.restype = c.c_int
         lib.fddo_block_commit.argtypes = [c.c_int] * 7 + [c.c_void_p] * 4
         lib.fddo_verify_step.restype = c.c_int
@@ -220,6 +222,20 @@ def block_commit(block_k, block_v, ext_k, ext_v, E):
     if rc:
         raise ValueError("fddo_block_commit rejected its arguments")
     return ext_k, ext_v
+
+
+def traj_mean(traj):
+    """Equal-weight mean over the N rollout trajectories; traj [N, ...] float32/float64 -> float64 [...]."""
+    traj = np.ascontiguousarray(traj)
+    if traj.dtype not in (np.float32, np.float64):
+        raise TypeError("trajectories are float32 or float64")
+    N = traj.shape[0]
+    P = int(np.prod(traj.shape[1:]))
+    out = np.empty(traj.shape[1:], dtype=np.float64)
+    rc = _load().fddo_traj_mean(N, P, _DT[traj.dtype], _ptr(traj), _ptr(out))
+    if rc:
+        raise ValueError("fddo_traj_mean rejected its arguments")
+    return out
 
 
 def fork_block(src, N):

@@ -39,6 +39,14 @@
  *  fddo_block_commit    A finished block joins its rollout's extension: rows
  *                       E .. E+B-1 of ext[n] become block[n] (a pure copy).
  *
+ *  fddo_traj_mean       Trajectory averaging (paper, "Trajectory averaging",
+ *                       the merge equation): the output trajectory is the
+ *                       equal-weight mean of the N rollout trajectories,
+ *                       tau_out = (1/N) sum_i tau^(i), waypoint by waypoint.
+ *                       (The jerk-minimizing fit that turns a decoded rollout
+ *                       into 20 waypoints is not specified in the paper and is
+ *                       outside this file.)
+ *
  *  fddo_verify_step     The accept rule of the same step 3: value positions
  *                       are visited left to right; a draft token equal to the
  *                       arg max of the AR distribution at its position is
@@ -417,6 +425,18 @@ int fddo_verify_step(int N, int B, int64_t V, int dtype, const void *ar_logits, 
 {
     return fddo_verify_step_ex(N, B, V, dtype, ar_logits, scaffold, draft, mask, tokens, ar_tok, n_accepted, accepted,
                                0.0f, 0u);
+}
+
+/* out[p] = (1/N) sum_n traj[n, p]; traj is [N, P] (P = waypoints x coordinates), dtype 0 or 1. */
+int fddo_traj_mean(int N, int P, int dtype, const void *traj, double *out)
+{
+    if (N <= 0 || P <= 0 || (dtype != 0 && dtype != 1)) return 1;
+    for (int p = 0; p < P; ++p) {
+        double acc = 0.0;
+        for (int n = 0; n < N; ++n) acc += widen(traj, dtype, (size_t)n * P + p);
+        out[p] = acc / (double)N;
+    }
+    return 0;
 }
 
 /* K/V rows of just-committed positions <- table row (token mod T). */
