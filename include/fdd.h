@@ -265,6 +265,14 @@ typedef struct fdd_commit_params {
 
 fdd_status fdd_block_commit(const fdd_commit_params *p);
 
+/* fdd_traj_mean: trajectory averaging (paper, "Trajectory averaging", the merge
+ * equation): out[p] = (1/N) sum_n traj[n,p], p in [0,P), P = waypoints x
+ * coordinates.  fp32 in and out; the sum runs over n in ascending order in
+ * fp32, so the result is reproducible and within N * 2^-24 relative of the
+ * exact mean of the absolute values.  (The jerk-minimizing fit that produces
+ * the waypoints of a rollout is not specified by the paper and is not here.) */
+fdd_status fdd_traj_mean(int32_t N, int32_t P, const float *traj, float *out, void *stream);
+
 /* fdd_block_kv_update: refresh the K/V rows of positions committed by the
  * last unmask step.  No model is inside this library, so the new row of a
  * position holding token t is row (t mod T) of caller-provided tables: a

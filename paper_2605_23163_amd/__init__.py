@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     fdd_prefix_pack,
     fdd_prefix_pack_bytes,
     fdd_profile_attn_events,
+    fdd_traj_mean,
     fdd_unmask_step,
     fdd_unmask_workspace,
     fdd_verify_step,

@@ -17,7 +17,7 @@ FDD_F32, FDD_BF16 = 0, 1
 FDD_ATTN_CAUSAL_BLOCK = 1
 EXPORTS = ("fdd_block_attn_workspace", "fdd_block_attn", "fdd_prefix_pack_bytes", "fdd_prefix_pack",
            "fdd_unmask_workspace", "fdd_unmask_step", "fdd_verify_workspace", "fdd_verify_step",
-           "fdd_fork_block", "fdd_block_kv_update", "fdd_block_commit", "fdd_profile_attn_events", "fdd_last_error", "fdd_version")
+           "fdd_fork_block", "fdd_block_kv_update", "fdd_block_commit", "fdd_traj_mean", "fdd_profile_attn_events", "fdd_last_error", "fdd_version")
 
 
 class FddError(RuntimeError):
@@ -102,6 +102,8 @@ def load_library():
         lib.fdd_fork_block.argtypes = [C.c_int32, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.fdd_block_kv_update.restype = C.c_int
         lib.fdd_block_kv_update.argtypes = [C.POINTER(KvUpdateParams)]
+        lib.fdd_traj_mean.restype = C.c_int
+        lib.fdd_traj_mean.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.fdd_block_commit.restype = C.c_int
         lib.fdd_block_commit.argtypes = [C.POINTER(CommitParams)]
         lib.fdd_profile_attn_events.restype = C.c_int
@@ -370,3 +372,17 @@ def fdd_block_commit(block_k, block_v, ext_k, ext_v, E, stream=None):
     p.stream = _stream_ptr(stream)
     _check(lib.fdd_block_commit(C.byref(p)))
     return int(E) + B
+
+
+def fdd_traj_mean(traj, out=None, stream=None):
+    """Equal-weight mean of the N rollout trajectories: traj [N, ...] float32 -> [...]."""
+    import torch
+    lib = load_library()
+    if traj.dtype != torch.float32:
+        raise TypeError("trajectories are float32")
+    N = traj.shape[0]
+    P = traj[0].numel()
+    if out is None:
+        out = torch.empty(traj.shape[1:], dtype=torch.float32, device=traj.device)
+    _check(lib.fdd_traj_mean(N, P, _dev(traj, "traj"), _dev(out, "out"), _stream_ptr(stream)))
+    return out

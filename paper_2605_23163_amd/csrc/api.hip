@@ -313,6 +313,17 @@ fdd_status fdd_block_commit(const fdd_commit_params* p)
     return FDD_OK;
 }
 
+fdd_status fdd_traj_mean(int32_t N, int32_t P, const float* traj, float* out, void* stream)
+{
+    if (!traj || !out) return fail(FDD_ERR_NULL, "fdd_traj_mean: traj and out must not be NULL");
+    if (N <= 0 || P <= 0) return fail(FDD_ERR_SHAPE, "fdd_traj_mean: N and P must be positive (got N=%d P=%d)", N, P);
+    if ((reinterpret_cast<uintptr_t>(traj) & 3u) || (reinterpret_cast<uintptr_t>(out) & 3u))
+        return fail(FDD_ERR_UNSUPPORTED, "fdd_traj_mean: pointers must be 4-byte aligned");
+    hipError_t e = launch_traj_mean(N, P, traj, out, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_traj_mean: launch failed: %s", hipGetErrorString(e));
+    return FDD_OK;
+}
+
 fdd_status fdd_block_kv_update(const fdd_kv_update_params* p)
 {
     if (!p) return fail(FDD_ERR_NULL, "fdd_block_kv_update: params is NULL");

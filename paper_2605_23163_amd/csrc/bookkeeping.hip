@@ -60,7 +60,23 @@ __global__ __launch_bounds__(256) void commit_kernel(size_t block_vecs, size_t e
     }
 }
 
+// equal-weight mean of the N rollout trajectories, one thread per coordinate
+__global__ __launch_bounds__(256) void traj_mean_kernel(int N, int P, const float* traj, float* out)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= P) return;
+    float acc = 0.f;
+    for (int n = 0; n < N; ++n) acc += traj[(size_t)n * P + p];
+    out[p] = acc / (float)N;
+}
+
 }  // namespace
+
+hipError_t launch_traj_mean(int N, int P, const float* traj, float* out, hipStream_t s)
+{
+    hipLaunchKernelGGL(traj_mean_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s, N, P, traj, out);
+    return hipGetLastError();
+}
 
 hipError_t launch_block_commit(const fdd_commit_params& p, hipStream_t s)
 {

@@ -78,5 +78,6 @@ hipError_t launch_verify(const fdd_verify_params& p, const UnmaskPlan& plan, hip
 hipError_t launch_fork_block(int N, size_t bytes, const void* src, void* dst, hipStream_t s);
 hipError_t launch_kv_update(const fdd_kv_update_params& p, hipStream_t s);
 hipError_t launch_block_commit(const fdd_commit_params& p, hipStream_t s);
+hipError_t launch_traj_mean(int N, int P, const float* traj, float* out, hipStream_t s);
 
 }  // namespace fdd

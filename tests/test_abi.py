@@ -169,6 +169,14 @@ def test_extension_and_commit_errors(lib):
     assert lib.fdd_block_commit(None) == 1
 
 
+def test_traj_mean_errors(lib):
+    assert lib.fdd_traj_mean(4, 40, None, 4096, None) == 1
+    assert lib.fdd_traj_mean(0, 40, 256, 4096, None) == 2
+    assert lib.fdd_traj_mean(4, 0, 256, 4096, None) == 2
+    assert lib.fdd_traj_mean(4, 40, 258, 4096, None) == 4
+    assert lib.fdd_last_error().decode().startswith("fdd_traj_mean:")
+
+
 def test_binding_refuses_host_tensors():
     import torch
     q = torch.zeros(1, 8, 4, 64)
