@@ -206,6 +206,56 @@ def time_spec_verify(F, w, d, g, logits, steps, warmup):
     }
 
 
+def time_layer_sweep_graph(F, w, n_layers, replays):
+    """One decode step's worth of attention at N=1: `n_layers` calls on distinct
+    prefix buffers (as the layers of a step are), recorded once into a HIP graph
+    and replayed, which takes the per-call launch work off the host."""
+    import torch
+    import fdd_workloads as W
+    d = W.attention_inputs(w)
+    q, bk, bv = dev(d["q"]), dev(d["block_k"]), dev(d["block_v"])
+    pk0, pv0 = dev(d["prefix_k"]), dev(d["prefix_v"])
+    pks = [pk0] + [pk0.clone() for _ in range(n_layers - 1)]
+    pvs = [pv0] + [pv0.clone() for _ in range(n_layers - 1)]
+    packs = [F.fdd_prefix_pack(v) for v in pvs]
+    outs = [torch.empty_like(q) for _ in range(n_layers)]
+    ws = torch.empty(max(256, F.fdd_block_attn_workspace(q, pk0, pv0, bk, bv, prefix_v_packed=packs[0])), dtype=torch.uint8,
+                     device="cuda")
+
+    def sweep():
+        for l in range(n_layers):
+            F.fdd_block_attn(q, pks[l], pvs[l], bk, bv, out=outs[l], workspace=ws, prefix_v_packed=packs[l])
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        sweep()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        sweep()
+    times = {}
+    for name, fn in (("eager", sweep), ("graph", graph.replay)):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0.record()
+        for _ in range(replays):
+            fn()
+        t1.record()
+        torch.cuda.synchronize()
+        times[name] = t0.elapsed_time(t1) / replays / n_layers
+    prefix, _ = attn_bytes(w)
+    return {"workload": f"N={w.N} B={w.B} L={w.L} Hq={w.Hq} Hkv={w.Hkv} D={w.D} bf16, {n_layers} layers back to back "
+                        f"on distinct prefix buffers, prefix V laid out beforehand",
+            "eager_us_per_layer": round(times["eager"] * 1e3, 2), "graph_us_per_layer": round(times["graph"] * 1e3, 2),
+            "prefix_GBs_graph": round(prefix / (times["graph"] * 1e-3) / 1e9, 1),
+            "frac_peak_hbm_graph": round(prefix / (times["graph"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "rollout_tokens_per_s_graph": round(w.N * w.B / (times["graph"] * 1e-3), 1)}
+
+
 def time_extension(F, w, d, g, steps, warmup):
     """Third block of the trajectory section: every rollout has committed two
     blocks of its own since the fork (E = 2B extension rows), plus the commit."""
@@ -399,6 +449,8 @@ def main():
         res["n1_prefix_stream"] = time_attention_only(F, n1, 400, 40, 128)
         n1_long = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
         res["n1_prefix_stream_L16384"] = time_attention_only(F, n1_long, 200, 20, 20)
+        res["n1_layer_sweep"] = time_layer_sweep_graph(F, n1, 28, 20)
+        res["n1_layer_sweep_L16384"] = time_layer_sweep_graph(F, n1_long, 28, 10)
         if has_unmask:
             res["spec_verify"] = time_spec_verify(F, w, d, g, logits, 100, 10)
         res["extension_block"] = time_extension(F, w, d, g, 50, 5)

@@ -19,22 +19,24 @@
 //     operand of O^T += V^T P^T, so P never leaves the register file and the
 //     accumulator keeps one query row per lane: its rescale is a per-lane
 //     scalar multiply.
+//   * Every K/V tile goes from global memory straight into LDS
+//     (buffer_load ... lds: no registers, no vector ALU work, no LDS writes by
+//     the waves) into a ring of 4 K slots and 4 V slots.  K tiles lie
+//     [key][d] with the 16-byte pieces of a row XOR-swizzled by the row index,
+//     which keeps the K fragment reads conflict-free without padding.
 //   * O^T += V^T P^T needs, per lane, 8 keys of one channel, i.e. V with the
-//     key index contiguous, while V lies in memory [key][d].  When an M-tile's
-//     keys are streamed by more than one workgroup (R > 256 rows per KV head),
-//     a small pre-pass packs the full prefix tiles of V once into the exact
-//     fragment order, [tile][16-key step][half][d][8 keys], so the main kernel
-//     moves those 16 KB tiles straight from global memory into LDS
-//     (buffer_load ... lds, no registers, no vector ALU work) and reads
-//     fragments as plain conflict-free 128-bit loads.  K tiles take the same
-//     direct path, [key][d] with the 16-byte pieces of a row XOR-swizzled by
-//     the row index, which keeps the K fragment reads conflict-free without
-//     padding.  Otherwise (a single M-tile per head, the ragged last prefix
-//     tile, the in-block tail) tiles are staged through registers as they lie
-//     in memory and V^T fragments come from the gfx950 LDS transpose read
-//     (ds_read_b64_tr_b16: lane i of a 16-lane group receives column i of a
-//     4 x 16 block, i.e. 4 consecutive keys of channel i); row pads of 16
-//     bytes (K) and 64 bytes (V) make both kinds of read conflict-free.
+//     key index contiguous, while V lies in memory [key][d].  Where an
+//     M-tile's keys are streamed by more than one workgroup (R > 256 rows per
+//     KV head), or the caller did it once for the prefix, the full prefix
+//     tiles of V are packed into the exact fragment order,
+//     [tile][16-key step][half][d][8 keys], and read back as plain
+//     conflict-free 128-bit loads.  V tiles that are moved as they lie (a
+//     single M-tile per head, the ragged last prefix tile, a rollout's private
+//     tiles) are read with the gfx950 LDS transpose read (ds_read_b64_tr_b16:
+//     lane i of a 16-lane group receives column i of a 4 x 16 block, i.e. 4
+//     consecutive keys of channel i); their 32-byte columns are XOR-swizzled
+//     by the row on the global side of the load, which makes those reads
+//     conflict-free too.
 //   * Full prefix tiles run through a software-pipelined loop written as 32
 //     slots per tile, one per MFMA.  Each slot also carries a slice of vector
 //     ALU work that does not depend on that MFMA: while the matrix pipe
@@ -42,26 +44,34 @@
 //     the vector ALUs reduce the row maximum of tile i, take its exponentials
 //     and round them to bf16.  One wavefront can only issue a vector
 //     instruction every other issue slot, so two wavefronts per SIMD running
-//     this same mix are what fills both pipes.  K runs one tile ahead of V in
-//     LDS (two buffers each), global loads another tile ahead in registers,
-//     and LDS fragments are requested two MFMAs before their use.
+//     this same mix are what fills both pipes.  Tile i+3 is requested at the
+//     start of step i and waits are counted (the loads of a wavefront complete
+//     in issue order), so two tiles stay in flight across a step; LDS
+//     fragments are requested two MFMAs before their use.  The loop is
+//     unrolled four times so that ring slots are immediate offsets.
 //   * The softmax reference value of a row is only raised when the running
 //     maximum outgrows it by more than 2^8; in between probabilities may
 //     exceed 1, which fp32 sums and bf16 relative precision do not mind, and
 //     the accumulator rescale becomes a rare wave-uniform branch.  The result
 //     is mathematically the same softmax.
-//   * Work is dealt out stream-K style.  The unit of work is one 64-key prefix
-//     tile of one M-tile; all units, ordered by (KV head, M-tile, tile), are
-//     cut into W equal contiguous ranges, one per workgroup, so every compute
-//     unit gets the same amount of work whatever the shape.  A range may end
-//     inside an M-tile and continue in the next one: each such segment keeps
-//     its own streaming-softmax state (m, l, o) per row.  An M-tile that was
-//     covered by a single segment is normalised and written as bf16 output
-//     directly; otherwise the segments leave fp32 partials that a second small
-//     kernel merges (log-sum-exp merge, fixed order).
-//   * A ragged last prefix tile and the in-block tail go through a simpler
-//     masked path: the workgroup stages the block K/V of each rollout its
-//     rows belong to and masks the rows of other rollouts to -inf.
+//   * Work is dealt out in units of one 64-key prefix tile of one M-tile.
+//     Either every M-tile is cut into S equal pieces (workgroups numbered so
+//     that an XCD owns all M-tiles of one (KV head, piece): they walk the same
+//     keys in step and the XCD's L2 serves all but the first fetch), or all
+//     units, ordered by (KV head, M-tile, tile), are cut into W contiguous
+//     ranges, one per workgroup (stream-K), so every compute unit gets the
+//     same amount of work whatever the shape.  A range may end inside an
+//     M-tile and continue in the next one: each such segment keeps its own
+//     streaming-softmax state (m, l, o) per row.  An M-tile that was covered
+//     by a single segment is normalised and written as bf16 output directly;
+//     otherwise the segments leave fp32 partials that a second small kernel
+//     merges (log-sum-exp merge, fixed order).
+//   * The ragged last prefix tile and the private tiles of every rollout the
+//     M-tile's rows belong to (the rows that rollout committed since the fork,
+//     then its live block: paper, "Shared prefix" and "Block-Causal
+//     Diffusion") go through a simpler masked path out of the same ring: rows
+//     of other rollouts are masked to -inf, and in the verify pass of scaffold
+//     speculative decoding the block keys after the query's own position too.
 #include <type_traits>
 
 #include "fdd_internal.h"
