@@ -268,7 +268,8 @@ def time_extension(F, w, d, g, steps, warmup):
     out = torch.empty_like(g["q"])
     packed_v = F.fdd_prefix_pack(g["prefix_v"])
     ws = torch.empty(max(256, F.fdd_block_attn_workspace(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"],
-                                                         prefix_v_packed=packed_v)), dtype=torch.uint8, device="cuda")
+                                                         prefix_v_packed=packed_v, ext_k=ext[0], ext_v=ext[1], E=E)),
+                     dtype=torch.uint8, device="cuda")
     ev = Events(steps)
     for i in range(warmup + steps):
         if i >= warmup:

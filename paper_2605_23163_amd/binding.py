@@ -225,9 +225,11 @@ def fdd_prefix_pack(prefix_v, packed=None, stream=None):
     return packed
 
 
-def fdd_block_attn_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0, prefix_v_packed=None) -> int:
-    # (the per-rollout extension does not change the workspace size)
-    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, None, None, None, splits, prefix_v_packed)
+def fdd_block_attn_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0, prefix_v_packed=None,
+                             ext_k=None, ext_v=None, E=0) -> int:
+    """Workspace bytes of the fdd_block_attn call with these arguments (E counts: the work split depends on it)."""
+    p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, None, None, None, splits, prefix_v_packed, False,
+                     ext_k, ext_v, E)
     return load_library().fdd_block_attn_workspace(C.byref(p))
 
 

@@ -43,7 +43,7 @@ fdd_status check_attn_shape(const fdd_attn_params* p)
     {
         // work units of the bf16 path: (KV head, 256-row M-tile, 64-key prefix tile)
         const long long mt = ((long long)p->N * p->B * (p->Hq / p->Hkv) + 255) / 256;
-        const long long tpu = p->L > 0 ? (p->L + 63) / 64 : 1;
+        const long long tpu = (p->L + 63) / 64 + 64;          // prefix tiles plus the units booked for private tiles (bounded by 64 here)
         if (p->Hkv * mt * tpu >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq*L too large");
     }
     if (std::isnan(p->scale) || std::isinf(p->scale)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: scale is not finite");
@@ -70,41 +70,77 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
     }
     pl.MT = (pl.R + pl.mtile_rows - 1) / pl.mtile_rows;
     pl.TP = (p.L + pl.key_tile - 1) / pl.key_tile;
-    pl.TPU = pl.TP > 0 ? pl.TP : 1;
     const long long NM = (long long)p.Hkv * pl.MT;
-    pl.U = NM * pl.TPU;
     bool partials;
     if (p.dtype == FDD_BF16) {
+        // The private tiles of an M-tile (extension and block of every rollout its rows belong to) are done
+        // by the workgroup that ends the M-tile's key range, one after the other and at about 1.8 times the
+        // cost of a pipelined prefix tile.  They are booked as `wt` extra units at the end of the M-tile's
+        // unit range, so that this workgroup gets correspondingly fewer prefix tiles.
+        const long long BG = (long long)p.B * pl.G;
+        const long long span_lo = (pl.mtile_rows + BG - 1) / BG;                 // rollouts an M-tile spans at least
+        const long long span = span_lo + ((pl.mtile_rows % BG) != 0 && BG < (long long)pl.R ? 1 : 0);
+        const long long private_tiles = (span < p.N ? span : p.N) *
+                                        ((p.E + pl.key_tile - 1) / pl.key_tile + (p.B + pl.key_tile - 1) / pl.key_tile);
+        long long wt = (private_tiles * 9 + 4) / 5;
+        if (wt < 1) wt = 1;
+        if (wt > 64) wt = 64;
+        auto pieces_for = [&](long long tpu) {
+            // equal pieces per M-tile, at least two units each; the fewest pieces that reach the shortest critical path
+            long long smax = NM > 0 ? kNumCU / NM : 0;
+            if (smax > tpu / 2) smax = tpu / 2;
+            if (smax < 1) return 0ll;
+            const long long crit = (tpu + smax - 1) / smax;
+            long long sbest = smax;
+            while (sbest > 1 && (tpu + (sbest - 1) - 1) / (sbest - 1) == crit) --sbest;
+            return sbest;
+        };
         long long w;
         pl.uniform = 0;
         if (p.splits > 0) {
+            if (wt > 2) wt = 2;
+            pl.TPU = pl.TP + (int)wt;
             pl.uniform = p.splits < pl.TPU ? p.splits : pl.TPU;
             w = NM * pl.uniform;
         } else {
             // Equal pieces per M-tile when that fills at least 4/5 of the compute
             // units: the workgroups of an XCD then walk the same K/V tiles in step
             // and the prefix is fetched from HBM once.  Otherwise equal contiguous
-            // unit ranges (stream-K), two tiles or more per workgroup.
-            long long s = NM > 0 ? kNumCU / NM : 0;
-            if (s > pl.TPU / 2) s = pl.TPU / 2;
-            if (s >= 1 && NM * s * 5 >= (long long)kNumCU * 4) {
+            // unit ranges (stream-K), two units or more per workgroup.
+            long long s = pieces_for(pl.TP + wt);
+            if (s >= 1) {
+                const long long per = (pl.TP + wt) / s;       // a piece must not lie inside the booked units only
+                if (wt > per) wt = per > 1 ? per : 1;
+                s = pieces_for(pl.TP + wt);
+            }
+            pl.TPU = pl.TP + (int)wt;
+            long long smax = NM > 0 ? kNumCU / NM : 0;
+            if (smax > pl.TPU / 2) smax = pl.TPU / 2;
+            if (s >= 1 && NM * smax * 5 >= (long long)kNumCU * 4) {
                 w = NM * s;
                 pl.uniform = (int)s;
             } else {
-                w = pl.U < 2 * kNumCU ? (pl.U + 1) / 2 : kNumCU;
-                if (w > pl.U) w = pl.U;
+                // (ranges are short here: book at most two units, so that no range lies inside them only)
+                if (wt > 2) wt = 2;
+                pl.TPU = pl.TP + (int)wt;
+                const long long U = NM * pl.TPU;
+                w = U < 2 * kNumCU ? (U + 1) / 2 : kNumCU;
+                if (w > U) w = U;
                 if (w <= NM && NM <= kNumCU) {   // nothing to gain from cutting M-tiles: one workgroup each
                     w = NM;
                     pl.uniform = 1;
                 }
             }
         }
+        pl.U = NM * pl.TPU;
         pl.W = (int)w;
         pl.splits = 0;
         const long long upw = pl.U / pl.W;
-        pl.max_seg = (int)((pl.TPU + upw - 1) / upw) + 1;
+        pl.max_seg = pl.uniform > 0 ? pl.uniform : (int)((pl.TPU + upw - 1) / upw) + 1;
         partials = pl.W != NM;
     } else {
+        pl.TPU = pl.TP > 0 ? pl.TP : 1;
+        pl.U = NM * pl.TPU;
         int s = p.splits;
         if (s == 0) {
             s = (int)(kNumCU / NM);

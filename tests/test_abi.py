@@ -54,8 +54,8 @@ def test_attn_workspace_is_host_arithmetic(lib):
     p1 = attn(splits=1)
     assert lib.fdd_block_attn_workspace(C.byref(p1)) == 0
     p4 = attn(splits=4)
-    # 4 KV heads x 1 M-tile x (4 segments + 1 spare slot) x 256 rows x (128 + 2) floats
-    assert lib.fdd_block_attn_workspace(C.byref(p4)) == 4 * 5 * 256 * 130 * 4
+    # 4 KV heads x 1 M-tile x 4 segments x 256 rows x (128 + 2) floats
+    assert lib.fdd_block_attn_workspace(C.byref(p4)) == 4 * 4 * 256 * 130 * 4
     assert lib.fdd_block_attn_workspace(C.byref(attn(Hq=30))) == 0     # invalid -> 0
 
 
@@ -150,9 +150,10 @@ def test_extension_and_commit_errors(lib):
                      (dict(E=8, ext_capacity=1 << 30, ext_k=2048, ext_v=2304), 2)]:
         assert lib.fdd_block_attn(C.byref(attn(**kw))) == code, kw
         assert lib.fdd_last_error().decode().startswith("fdd_block_attn:")
-    # E = 0 ignores the extension pointers; the workspace does not depend on E
-    assert lib.fdd_block_attn_workspace(C.byref(attn(E=64, ext_capacity=64, ext_k=2048, ext_v=2304))) == \
+    # E = 0 ignores the extension pointers
+    assert lib.fdd_block_attn_workspace(C.byref(attn(E=0, ext_capacity=64, ext_k=2048, ext_v=2304))) == \
         lib.fdd_block_attn_workspace(C.byref(attn()))
+    assert lib.fdd_block_attn_workspace(C.byref(attn(E=64, ext_capacity=64, ext_k=2048, ext_v=2304))) > 0
 
     def cp(**kw):
         p = bd.CommitParams()

@@ -57,7 +57,8 @@ def test_step_replays_from_a_hip_graph(F):
     tmean = torch.empty((20, 2), dtype=torch.float32, device="cuda")
     packed = torch.empty(F.fdd_prefix_pack_bytes(g["prefix_v"]), dtype=torch.uint8, device="cuda")
     ws_a = torch.empty(max(256, F.fdd_block_attn_workspace(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"],
-                                                           splits=4, prefix_v_packed=packed)), dtype=torch.uint8, device="cuda")
+                                                           splits=4, prefix_v_packed=packed, ext_k=ext_k, ext_v=ext_v, E=w.B)),
+                       dtype=torch.uint8, device="cuda")
     ws_u = torch.empty(max(256, F.fdd_unmask_workspace(logits)), dtype=torch.uint8, device="cuda")
 
     def step():
