@@ -22,7 +22,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + os.path.j
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 # The attention kernels never produce a NaN (masked scores are -inf and every
 # inf - inf is avoided by construction), so max/min need no NaN quieting.
-EXTRA = {"attn_bf16.hip": ["-fno-honor-nans", "-mno-amdgpu-ieee"]}
+EXTRA = {"attn_bf16.hip": ["-fno-honor-nans", "-mno-amdgpu-ieee"], "unmask.hip": ["-fno-honor-nans", "-mno-amdgpu-ieee"]}
 
 
 def sources():
