@@ -42,7 +42,7 @@ STEPS_PER_BLOCK = 8
 # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each scaled
 # by what the same counter reads for a 1 GiB device copy (0.5x and 1.0x); summary and commands in
 # profiles/bench_cfg5_denoise_step.md.  (read MiB, write MiB) per launch.
-MEASURED_TRAFFIC_MIB = {"cfg5": {"attn_bf16_kernel": (50.1, 31.1), "vocab_reduce_kernel": (193.0, 0.1)}}
+MEASURED_TRAFFIC_MIB = {"cfg5": {"attn_bf16_kernel": (48.3, 28.4), "vocab_reduce_kernel": (193.0, 0.1)}}
 
 
 def dev(a):
@@ -329,6 +329,8 @@ def main():
     ap.add_argument("--workload", default="cfg5", choices=["cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-supplements", action="store_true")
+    ap.add_argument("--n1-only", action="store_true",
+                    help="run only the N=1 layer sweeps (for profiling them) and print their figures")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
@@ -341,6 +343,13 @@ def main():
         sys.exit("bench.py needs a GPU")
     F.load_library()
     torch.cuda.set_device(0)
+
+    if args.n1_only:
+        n1 = W.CONFIGS["cfg2"]
+        n1_long = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
+        print(json.dumps({"n1_layer_sweep": time_layer_sweep_graph(F, n1, 28, 20),
+                          "n1_layer_sweep_L16384": time_layer_sweep_graph(F, n1_long, 28, 10)}))
+        return
 
     w = W.CONFIGS[args.workload]
     d = W.full_step_inputs(w, n_logit_steps=2)
