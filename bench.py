@@ -316,7 +316,8 @@ def cpu_baseline(w, d, logits):
         "value": round(w.N * w.B / t_step, 2), "unit": "rollout-tokens/s", "cores": oracle.num_threads(),
         "kind": "oracle",
         "sample": f"attention on {len(idx)} of {rows_all} output rows (every {stride}th) and unmask on {n_un} of "
-                  f"{w.N} blocks of one step, each scaled to the full step; est. {t_step:.1f} s per step",
+                  f"{w.N} blocks of one step, each scaled to the full step; est. {t_step:.1f} s per step "
+                  f"({(t_attn * len(idx) / rows_all + t_un * n_un / max(w.N, 1)) * oracle.num_threads():.0f} core-seconds spent)",
         "host_cpu_count": os.cpu_count(),
     }
 
