@@ -256,6 +256,48 @@ def time_layer_sweep_graph(F, w, n_layers, replays):
             "rollout_tokens_per_s_graph": round(w.N * w.B / (times["graph"] * 1e-3), 1)}
 
 
+def time_batched(F, w, P, reps):
+    """P independent N=1 problems (each with its own prefix) in ONE launch: the prefix stream without the
+    per-launch latencies that bound a single small problem."""
+    import torch
+    import fdd_workloads as W
+    d = W.attention_inputs(w)
+    rep = lambda a: dev(a).unsqueeze(0).repeat(P, *([1] * a.ndim)).contiguous()
+    q, pk, pv, bk, bv = (rep(d[k]) for k in ("q", "prefix_k", "prefix_v", "block_k", "block_v"))
+    pk += torch.randn(P, 1, 1, 1, device="cuda").to(pk.dtype) * 0.01       # the prefixes differ
+    packed = torch.stack([F.fdd_prefix_pack(pv[i]) for i in range(P)])
+    out = torch.empty_like(q)
+    ws = torch.empty(max(256, F.fdd_block_attn_batched_workspace(q, pk, pv, bk, bv, prefix_v_packed=packed)),
+                     dtype=torch.uint8, device="cuda")
+    # rotate over copies of the prefixes so that they come from HBM, not from the last-level cache
+    n_sets = max(2, int(600e6 // (2 * pk.numel() * 2)) + 1)
+    sets = [(pk, packed)] + [(pk.clone(), packed.clone()) for _ in range(n_sets - 1)]
+    ev = Events(reps)
+    for i in range(3):
+        F.fdd_block_attn_batched(q, sets[i % n_sets][0], pv, bk, bv, out=out, workspace=ws, prefix_v_packed=sets[i % n_sets][1])
+    torch.cuda.synchronize()
+    t0, t1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for i in range(reps):
+        F.fdd_profile_attn_events(*ev.pairs[i])
+        F.fdd_block_attn_batched(q, sets[i % n_sets][0], pv, bk, bv, out=out, workspace=ws, prefix_v_packed=sets[i % n_sets][1])
+    t1.record()
+    torch.cuda.synchronize()
+    F.fdd_profile_attn_events(None, None)
+    call_ms, kern_ms = t0.elapsed_time(t1) / reps, ev.mean_ms(reps)
+    prefix = attn_bytes(w)[0] * P
+    flops = attn_flops(w) * P
+    return {"workload": f"{P} independent problems of N={w.N} B={w.B} L={w.L} Hq={w.Hq} Hkv={w.Hkv} D={w.D} bf16 in one "
+                        f"launch, {n_sets} sets of prefixes in rotation, prefix V laid out beforehand",
+            "call_us": round(call_ms * 1e3, 2), "kernel_us": round(kern_ms * 1e3, 2), "prefix_bytes": prefix,
+            "prefix_GBs_kernel": round(prefix / (kern_ms * 1e-3) / 1e9, 1), "prefix_GBs_call": round(prefix / (call_ms * 1e-3) / 1e9, 1),
+            "frac_peak_hbm_kernel": round(prefix / (kern_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "frac_peak_hbm_call": round(prefix / (call_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+            "tflops_kernel": round(flops / (kern_ms * 1e-3) / 1e12, 1),
+            "frac_peak_mfma_kernel": round(flops / (kern_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "rollout_tokens_per_s": round(P * w.N * w.B / (call_ms * 1e-3), 1)}
+
+
 def time_extension(F, w, d, g, steps, warmup):
     """Third block of the trajectory section: every rollout has committed two
     blocks of its own since the fork (E = 2B extension rows), plus the commit."""
@@ -349,7 +391,9 @@ def main():
         n1 = W.CONFIGS["cfg2"]
         n1_long = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
         print(json.dumps({"n1_layer_sweep": time_layer_sweep_graph(F, n1, 28, 20),
-                          "n1_layer_sweep_L16384": time_layer_sweep_graph(F, n1_long, 28, 10)}))
+                          "n1_layer_sweep_L16384": time_layer_sweep_graph(F, n1_long, 28, 10),
+                          "n1_batched": time_batched(F, n1, 28, 50),
+                          "n1_batched_L16384": time_batched(F, n1_long, 8, 30)}))
         return
 
     w = W.CONFIGS[args.workload]
@@ -462,6 +506,8 @@ def main():
         res["n1_prefix_stream_L16384"] = time_attention_only(F, n1_long, 200, 20, 20)
         res["n1_layer_sweep"] = time_layer_sweep_graph(F, n1, 28, 20)
         res["n1_layer_sweep_L16384"] = time_layer_sweep_graph(F, n1_long, 28, 10)
+        res["n1_batched"] = time_batched(F, n1, 28, 50)
+        res["n1_batched_L16384"] = time_batched(F, n1_long, 8, 30)
         if has_unmask:
             res["spec_verify"] = time_spec_verify(F, w, d, g, logits, 100, 10)
         res["extension_block"] = time_extension(F, w, d, g, 50, 5)

@@ -109,6 +109,17 @@ typedef struct fdd_attn_params {
     const void *ext_v;             /* [N, ext_capacity, Hkv, D] */
     int32_t E;                     /* valid extension rows per rollout, 0 <= E <= ext_capacity */
     int32_t ext_capacity;          /* rows allocated per rollout */
+    /* Batch of independent problems of one shape in a single launch (for callers whose problems are each
+     * too small to fill the chip: several requests, each with its own prefix).  Problem i uses the arrays
+     * at q + i*q_batch_stride, prefix_k/prefix_v + i*prefix_batch_stride, block_k/block_v +
+     * i*block_batch_stride, ext_k/ext_v + i*ext_batch_stride, out + i*out_batch_stride (strides in
+     * elements, multiples of 8, at least the size of one problem's array) and prefix_v_packed +
+     * i*packed_batch_stride (bytes, a multiple of 256).  batch <= 1 is the single problem and the strides
+     * are ignored.  Nothing is shared between the problems of a batch. */
+    int32_t batch;
+    int32_t reserved;              /* must be 0 */
+    int64_t q_batch_stride, prefix_batch_stride, block_batch_stride, ext_batch_stride, out_batch_stride;
+    size_t packed_batch_stride;
 } fdd_attn_params;
 
 /* Bytes of scratch fdd_block_attn needs for these params (host-only

@@ -8,6 +8,8 @@ the first call loads the library and fails loudly if it has not been built.
 from .binding import (  # noqa: F401
     FddError,
     fdd_block_attn,
+    fdd_block_attn_batched,
+    fdd_block_attn_batched_workspace,
     fdd_block_attn_workspace,
     fdd_block_commit,
     fdd_block_kv_update,

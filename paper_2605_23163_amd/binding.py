@@ -34,7 +34,9 @@ class AttnParams(C.Structure):
                 ("out", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
                 ("stream", C.c_void_p), ("splits", C.c_int32), ("flags", C.c_int32),
                 ("prefix_v_packed", C.c_void_p), ("ext_k", C.c_void_p), ("ext_v", C.c_void_p),
-                ("E", C.c_int32), ("ext_capacity", C.c_int32)]
+                ("E", C.c_int32), ("ext_capacity", C.c_int32), ("batch", C.c_int32), ("reserved", C.c_int32),
+                ("q_batch_stride", C.c_int64), ("prefix_batch_stride", C.c_int64), ("block_batch_stride", C.c_int64),
+                ("ext_batch_stride", C.c_int64), ("out_batch_stride", C.c_int64), ("packed_batch_stride", C.c_size_t)]
 
 
 class UnmaskParams(C.Structure):
@@ -246,6 +248,53 @@ def fdd_block_attn(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask=None, 
         out = torch.empty_like(q)
     p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed,
                      causal_block, ext_k, ext_v, E)
+    need = lib.fdd_block_attn_workspace(C.byref(p))
+    ws, nbytes = _workspace(workspace, need, q.device)
+    p.workspace = ws.data_ptr() if ws is not None else None
+    p.workspace_bytes = nbytes
+    p.stream = _stream_ptr(stream)
+    _check(lib.fdd_block_attn(C.byref(p)))
+    return out
+
+
+def _batched_params(q, prefix_k, prefix_v, block_k, block_v, out, scale, splits, prefix_v_packed, causal_block, ext_k, ext_v, E):
+    """Parameters of a batch of independent problems: every array has a leading batch dimension."""
+    P = q.shape[0]
+    for name, t in (("prefix_k", prefix_k), ("prefix_v", prefix_v), ("block_k", block_k), ("block_v", block_v),
+                    ("out", out), ("ext_k", ext_k), ("ext_v", ext_v), ("prefix_v_packed", prefix_v_packed)):
+        if t is not None and (t.shape[0] != P or not t[0].is_contiguous()):
+            raise ValueError(f"{name} must have leading dimension {P} and contiguous problems")
+    sub = lambda t: None if t is None else t[0]
+    p = _attn_params(q[0], prefix_k[0], prefix_v[0], block_k[0], block_v[0], None, sub(out), scale, splits,
+                     sub(prefix_v_packed), causal_block, sub(ext_k), sub(ext_v), E)
+    p.batch = P
+    if prefix_k.stride(0) != prefix_v.stride(0) or block_k.stride(0) != block_v.stride(0) or \
+            (ext_k is not None and ext_k.stride(0) != ext_v.stride(0)):
+        raise ValueError("K and V arrays of a batch must share their batch stride")
+    p.q_batch_stride, p.out_batch_stride = q.stride(0), (out.stride(0) if out is not None else q[0].numel())
+    p.prefix_batch_stride, p.block_batch_stride = prefix_k.stride(0), block_k.stride(0)
+    p.ext_batch_stride = ext_k.stride(0) if ext_k is not None else 0
+    p.packed_batch_stride = prefix_v_packed.stride(0) * prefix_v_packed.element_size() if prefix_v_packed is not None else 0
+    return p
+
+
+def fdd_block_attn_batched_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0, prefix_v_packed=None,
+                                     ext_k=None, ext_v=None, E=0) -> int:
+    p = _batched_params(q, prefix_k, prefix_v, block_k, block_v, None, None, splits, prefix_v_packed, False, ext_k, ext_v, E)
+    return load_library().fdd_block_attn_workspace(C.byref(p))
+
+
+def fdd_block_attn_batched(q, prefix_k, prefix_v, block_k, block_v, out=None, scale=None, workspace=None, stream=None,
+                           splits=0, prefix_v_packed=None, causal_block=False, ext_k=None, ext_v=None, E=0):
+    """A batch of independent fdd_block_attn problems of one shape in a single launch.  Every array carries a
+    leading batch dimension: q [P,N,B,Hq,D], prefix_k/v [P,L,Hkv,D], block_k/v [P,N,B,Hkv,D], and
+    prefix_v_packed [P, fdd_prefix_pack_bytes] if given.  Nothing is shared between the problems."""
+    import torch
+    lib = load_library()
+    if out is None:
+        out = torch.empty_like(q)
+    p = _batched_params(q, prefix_k, prefix_v, block_k, block_v, out, scale, splits, prefix_v_packed, causal_block,
+                        ext_k, ext_v, E)
     need = lib.fdd_block_attn_workspace(C.byref(p))
     ws, nbytes = _workspace(workspace, need, q.device)
     p.workspace = ws.data_ptr() if ws is not None else None

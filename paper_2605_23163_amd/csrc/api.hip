@@ -44,9 +44,28 @@ fdd_status check_attn_shape(const fdd_attn_params* p)
         // work units of the bf16 path: (KV head, 256-row M-tile, 64-key prefix tile)
         const long long mt = ((long long)p->N * p->B * (p->Hq / p->Hkv) + 255) / 256;
         const long long tpu = (p->L + 63) / 64 + 64;          // prefix tiles plus the units booked for private tiles (bounded by 64 here)
-        if (p->Hkv * mt * tpu >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq*L too large");
+        if (p->Hkv * (p->batch > 1 ? p->batch : 1) * mt * tpu >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_block_attn: batch*N*B*Hq*L too large");
     }
     if (std::isnan(p->scale) || std::isinf(p->scale)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: scale is not finite");
+    if (p->batch < 0 || p->batch > 65535 / p->Hkv) return fail(FDD_ERR_SHAPE, "fdd_block_attn: batch=%d outside [0, 65535 / Hkv]", p->batch);
+    if (p->reserved != 0) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: reserved field must be 0");
+    if (p->batch > 1) {
+        const long long es = p->dtype == FDD_BF16 ? 2 : 4;
+        struct { const char* name; long long stride, need; } st[] = {
+            {"q_batch_stride", p->q_batch_stride, (long long)p->N * p->B * p->Hq * p->D},
+            {"out_batch_stride", p->out_batch_stride, (long long)p->N * p->B * p->Hq * p->D},
+            {"block_batch_stride", p->block_batch_stride, (long long)p->N * p->B * p->Hkv * p->D},
+            {"prefix_batch_stride", p->prefix_batch_stride, (long long)p->L * p->Hkv * p->D},
+            {"ext_batch_stride", p->ext_batch_stride, p->E > 0 ? (long long)p->N * p->ext_capacity * p->Hkv * p->D : 0},
+        };
+        for (const auto& x : st)
+            if (x.stride < x.need || (x.stride * es) % 16)
+                return fail(FDD_ERR_SHAPE, "fdd_block_attn: %s=%lld must be at least %lld elements and a multiple of 16 bytes",
+                            x.name, x.stride, x.need);
+        if (p->prefix_v_packed && (p->packed_batch_stride % 256 ||
+                                   p->packed_batch_stride < (size_t)p->Hkv * (p->L / 64) * 64 * p->D * 2))
+            return fail(FDD_ERR_SHAPE, "fdd_block_attn: packed_batch_stride must be a multiple of 256 and hold one packed prefix V");
+    }
     if (p->E < 0 || p->ext_capacity < 0 || p->E > p->ext_capacity)
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: need 0 <= E <= ext_capacity (got E=%d, ext_capacity=%d)", p->E, p->ext_capacity);
     if ((long long)p->N * p->ext_capacity * p->Hkv * p->D * 4 >= (1ll << 32))
@@ -70,7 +89,8 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
     }
     pl.MT = (pl.R + pl.mtile_rows - 1) / pl.mtile_rows;
     pl.TP = (p.L + pl.key_tile - 1) / pl.key_tile;
-    const long long NM = (long long)p.Hkv * pl.MT;
+    const int batch = p.batch > 1 ? p.batch : 1;
+    const long long NM = (long long)p.Hkv * batch * pl.MT;
     bool partials;
     if (p.dtype == FDD_BF16) {
         // The private tiles of an M-tile (extension and block of every rollout its rows belong to) are done
@@ -167,7 +187,7 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
     pl.ws_vt_bytes = 0;
     pl.packed = p.dtype == FDD_BF16 && p.L >= pl.key_tile && (pl.MT >= 2 || p.prefix_v_packed);
     if (pl.packed && !p.prefix_v_packed)
-        pl.ws_vt_bytes = (((size_t)p.Hkv * (p.L / pl.key_tile) * pl.key_tile * p.D * 2) + 255) & ~(size_t)255;
+        pl.ws_vt_bytes = (((size_t)p.Hkv * batch * (p.L / pl.key_tile) * pl.key_tile * p.D * 2) + 255) & ~(size_t)255;
     *plan = pl;
     return true;
 }

@@ -101,6 +101,8 @@ struct Args {
     const uint16_t* ek;   // per-rollout extension [N, Ecap, Hkv, D]
     const uint16_t* ev;
     int E, Ecap;
+    int batch;            // independent problems in this launch; element strides between their arrays:
+    long long q_bs, p_bs, vt_bs, b_bs, e_bs, o_bs;
     int N, B, L, Hq, Hkv, G, R, MT, TP;
     int TPF;        // full prefix tiles = L / 64
     int TPU;        // units per M-tile = max(TP, 1)
@@ -240,13 +242,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         k_voff[jn] = (uint32_t)r * stride2 + (uint32_t)(((lane % C::CH) ^ ((r / C::RPL) & (C::CH - 1))) * 16);
     }
     const uint32_t vp_voff = (uint32_t)(wave * C::NI * 1024 + lane * 16);
-    const __amdgpu_buffer_rsrc_t pk_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.pk), 0, (uint32_t)a.L * stride2, RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t pv_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.pv), 0, (uint32_t)a.L * stride2, RSRC_FLAGS);
-    const __amdgpu_buffer_rsrc_t vt_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(a.vt), 0, (uint32_t)(a.Hkv * a.TPF) * C::T_BYTES, RSRC_FLAGS);
-
     auto k_frag = [&](uint32_t kbase, int kb, int ks) -> bf16x8 {
         return *reinterpret_cast<const bf16x8*>(lds + (kbase + k_fragoff[ks]) + kb * 32 * D * 2);
     };
@@ -268,8 +263,17 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     for (; todo > 0; ++M, t_begin = 0) {
         const int t_end = min(a.TPU, t_begin + todo);
         todo -= t_end - t_begin;
-        const int kh = M / a.MT;
-        const int mt = M - kh * a.MT;
+        // M runs over (problem of the batch, KV head, M-tile)
+        const int khv = M / a.MT;
+        const int mt = M - khv * a.MT;
+        const int pb = a.batch > 1 ? khv / a.Hkv : 0;
+        const int kh = khv - pb * a.Hkv;
+        // (the arrays of problem pb are addressed where they are used: few of these pointers are live at a time)
+        const __amdgpu_buffer_rsrc_t pk_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(a.pk + pb * a.p_bs), 0, (uint32_t)a.L * stride2, RSRC_FLAGS);
+        const __amdgpu_buffer_rsrc_t pv_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>((PACKED ? a.vt + pb * a.vt_bs : a.pv + pb * a.p_bs)), 0,
+            PACKED ? (uint32_t)(a.Hkv * a.TPF) * C::T_BYTES : (uint32_t)a.L * stride2, RSRC_FLAGS);
         // stores of the previous segment are out of the way of the load counting below
         wait_vm<0>();
 
@@ -292,8 +296,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             if (C::NI > 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(pk_rsrc, (lds_void*)(kdst + 1024), 16, k_voff[C::NI - 1], soff, 0, 0);
             if (PACKED) {
                 const uint32_t voff = (uint32_t)(kh * a.TPF + t0 + j) * C::T_BYTES;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(vt_rsrc, (lds_void*)vdst, 16, vp_voff, voff, 0, 0);
-                if (C::NI > 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(vt_rsrc, (lds_void*)(vdst + 1024), 16, vp_voff + 1024, voff, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(pv_rsrc, (lds_void*)vdst, 16, vp_voff, voff, 0, 0);
+                if (C::NI > 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(pv_rsrc, (lds_void*)(vdst + 1024), 16, vp_voff + 1024, voff, 0, 0);
             } else {
                 int tid_f = tid;
                 FDD_PIN(tid_f);     // recomputed at every fetch rather than kept in registers
@@ -321,7 +325,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const int g = row_ok ? row - nb * a.G : 0;
         bf16x8 qf[KS];
         {
-            const uint16_t* qp = a.q + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D + half * 8;
+            const uint16_t* qp = a.q + pb * a.q_bs + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D + half * 8;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 u32x4 raw = {0u, 0u, 0u, 0u};
@@ -400,8 +404,8 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             const Tile t = tile_at(j);
             const uint32_t rows_in_array = t.src == 0 ? (uint32_t)a.L : t.src == 1 ? (uint32_t)(a.N * a.Ecap) : (uint32_t)(a.N * a.B);
             const uint32_t bytes = rows_in_array * stride2;
-            const uint16_t* const ksrc = t.src == 0 ? a.pk : t.src == 1 ? a.ek : a.bk;
-            const uint16_t* const vsrc = t.src == 0 ? a.pv : t.src == 1 ? a.ev : a.bv;
+            const uint16_t* const ksrc = t.src == 0 ? a.pk + pb * a.p_bs : t.src == 1 ? a.ek + pb * a.e_bs : a.bk + pb * a.b_bs;
+            const uint16_t* const vsrc = t.src == 0 ? a.pv + pb * a.p_bs : t.src == 1 ? a.ev + pb * a.e_bs : a.bv + pb * a.b_bs;
             const __amdgpu_buffer_rsrc_t k_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(ksrc), 0, bytes, RSRC_FLAGS);
             const __amdgpu_buffer_rsrc_t v_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(vsrc), 0, bytes, RSRC_FLAGS);
             const uint32_t soff = __builtin_amdgcn_readfirstlane((uint32_t)t.row_base * stride2 + (uint32_t)(kh * D * 2));
@@ -680,7 +684,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         if (row_ok) {
             if (n_seg == 1) {
                 const float inv = 1.f / l_tot;
-                uint16_t* op = a.out + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D;
+                uint16_t* op = a.out + pb * a.o_bs + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -730,13 +734,16 @@ struct PackCfg {
 };
 
 template <int D>
-__global__ __launch_bounds__(512) void vt_pack_kernel(const uint16_t* __restrict__ pv, uint16_t* __restrict__ vt,
-                                                       int Hkv, int TPF)
+__global__ __launch_bounds__(512) void vt_pack_kernel(const uint16_t* __restrict__ pv_all, uint16_t* __restrict__ vt_all,
+                                                       int Hkv, int TPF, long long p_bs, long long vt_bs)
 {
     using C = PackCfg<D>;
     constexpr int DB = D / 32;
     __shared__ __align__(16) unsigned char tile[C::V_BYTES];
-    const int t = blockIdx.x, kh = blockIdx.y;
+    // grid (tile, KV head of a problem of the batch)
+    const int t = blockIdx.x, pb = blockIdx.y / Hkv, kh = blockIdx.y - pb * Hkv;
+    const uint16_t* pv = pv_all + pb * p_bs;
+    uint16_t* vt = vt_all + pb * vt_bs;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, half = lane >> 5;
     const size_t kv_stride = (size_t)Hkv * D;
     const uint16_t* src = pv + (size_t)t * KT * kv_stride + (size_t)kh * D;
@@ -776,8 +783,8 @@ hipError_t launch(const Args& a, bool pack_now, hipStream_t stream, hipEvent_t b
         attr_done = true;
     }
     if (PACKED && pack_now) {
-        hipLaunchKernelGGL(vt_pack_kernel<D>, dim3(a.TPF, a.Hkv), dim3(512), 0, stream, a.pv, const_cast<uint16_t*>(a.vt),
-                           a.Hkv, a.TPF);
+        hipLaunchKernelGGL(vt_pack_kernel<D>, dim3(a.TPF, a.Hkv * a.batch), dim3(512), 0, stream, a.pv,
+                           const_cast<uint16_t*>(a.vt), a.Hkv, a.TPF, a.p_bs, a.vt_bs);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -812,6 +819,11 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.ek = static_cast<const uint16_t*>(p.ext_k);
     a.ev = static_cast<const uint16_t*>(p.ext_v);
     a.E = p.E; a.Ecap = p.ext_capacity;
+    a.batch = p.batch > 1 ? p.batch : 1;
+    a.q_bs = p.q_batch_stride; a.p_bs = p.prefix_batch_stride; a.b_bs = p.block_batch_stride;
+    a.e_bs = p.ext_batch_stride; a.o_bs = p.out_batch_stride;
+    // packed V: the caller's stride, or the in-call copies lying back to back in the workspace
+    a.vt_bs = pack_now ? (long long)p.Hkv * (p.L / 64) * 64 * p.D : (long long)(p.packed_batch_stride / 2);
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.TPF = p.L / 64;
     a.TPU = plan.TPU; a.W = plan.W; a.max_seg = plan.max_seg; a.S = plan.uniform;
@@ -831,8 +843,8 @@ hipError_t launch_prefix_pack(const void* prefix_v, int L, int Hkv, int D, void*
     if (TPF == 0) return hipSuccess;
     const uint16_t* src = static_cast<const uint16_t*>(prefix_v);
     uint16_t* dst = static_cast<uint16_t*>(packed);
-    if (D == 128) hipLaunchKernelGGL(vt_pack_kernel<128>, dim3(TPF, Hkv), dim3(512), 0, s, src, dst, Hkv, TPF);
-    else hipLaunchKernelGGL(vt_pack_kernel<64>, dim3(TPF, Hkv), dim3(512), 0, s, src, dst, Hkv, TPF);
+    if (D == 128) hipLaunchKernelGGL(vt_pack_kernel<128>, dim3(TPF, Hkv), dim3(512), 0, s, src, dst, Hkv, TPF, 0ll, 0ll);
+    else hipLaunchKernelGGL(vt_pack_kernel<64>, dim3(TPF, Hkv), dim3(512), 0, s, src, dst, Hkv, TPF, 0ll, 0ll);
     return hipGetLastError();
 }
 

@@ -28,6 +28,8 @@ struct Args {
     const float* ek;   // per-rollout extension [N, Ecap, Hkv, D]
     const float* ev;
     int E, Ecap;
+    int batch;         // independent problems in this launch; element strides between their arrays:
+    long long q_bs, p_bs, b_bs, e_bs, o_bs;
     int N, B, L, Hq, Hkv, G, R, MT, TP, S;
     int causal;   // in-block keys are visible up to the query's own position only
     float c;   // scale * log2(e)
@@ -46,7 +48,18 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
     const int tid = threadIdx.x;
     const int mt = blockIdx.x;
     const int split = blockIdx.y;
-    const int kh = blockIdx.z;
+    // grid z runs over (problem of the batch, KV head); the pointers are moved to the problem's arrays
+    const int khv = blockIdx.z;
+    const int pb = khv / a.Hkv;
+    const int kh = khv - pb * a.Hkv;
+    a.q += pb * a.q_bs;
+    a.pk += pb * a.p_bs;
+    a.pv += pb * a.p_bs;
+    a.bk += pb * a.b_bs;
+    a.bv += pb * a.b_bs;
+    a.ek += pb * a.e_bs;
+    a.ev += pb * a.e_bs;
+    a.out += pb * a.o_bs;
     const int BG = a.B * a.G;
 
     const int r_loc = tid / 16;         // row of this thread inside the workgroup tile
@@ -184,7 +197,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
 #pragma unroll
         for (int j = 0; j < DPT; ++j) op[j] = o[j] * inv;
     } else {
-        const size_t prow = (((size_t)kh * a.MT + mt) * a.S + split) * RT + r_loc;
+        const size_t prow = (((size_t)khv * a.MT + mt) * a.S + split) * RT + r_loc;
         float* wo = a.ws_o + prow * D + sub * DPT;
 #pragma unroll
         for (int j = 0; j < DPT; ++j) wo[j] = o[j];
@@ -203,7 +216,8 @@ struct CombineArgs {
     const float* ws_o;
     const float* ws_ml;
     void* out;
-    int Hq, G, R, MT, mrows, D, bf16;
+    int Hq, Hkv, G, R, MT, mrows, D, bf16;
+    long long o_bs;  // elements between the outputs of the problems of a batch
     int max_seg;     // slots per M-tile in the workspace
     int fixed_seg;   // > 0: every M-tile has this many segments; 0: stream-K ranges
     int TPU, base, rem;
@@ -222,7 +236,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(CombineArgs a)
     const int tid = (int)threadIdx.x;
     const int d4 = tid % d4n, sg = (tid / d4n) % a.SG, r = tid / (d4n * a.SG);
     const int M = (int)blockIdx.x;
-    const int kh = M / a.MT, mt = M - kh * a.MT;
+    const int khv = M / a.MT, mt = M - khv * a.MT;      // (problem of the batch, KV head), M-tile
+    const int pb = khv / a.Hkv, kh = khv - pb * a.Hkv;
     const int rit0 = (int)blockIdx.y * a.RB;
     int n_seg = a.fixed_seg;
     if (n_seg == 0) {
@@ -299,7 +314,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(CombineArgs a)
     if (!live) return;
     const float inv = 1.f / l;
     const int nb = row / a.G, g = row - nb * a.G;
-    const size_t off = ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * a.D + d4 * 4;
+    const size_t off = (size_t)(pb * a.o_bs) + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * a.D + d4 * 4;
     if (a.bf16) {
         typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
         bf16x4 w;
@@ -330,12 +345,15 @@ hipError_t launch_attn_f32(const fdd_attn_params& p, const AttnPlan& plan, float
     a.ek = static_cast<const float*>(p.ext_k);
     a.ev = static_cast<const float*>(p.ext_v);
     a.E = p.E; a.Ecap = p.ext_capacity;
+    a.batch = p.batch > 1 ? p.batch : 1;
+    a.q_bs = p.q_batch_stride; a.p_bs = p.prefix_batch_stride; a.b_bs = p.block_batch_stride;
+    a.e_bs = p.ext_batch_stride; a.o_bs = p.out_batch_stride;
     a.N = p.N; a.B = p.B; a.L = p.L; a.Hq = p.Hq; a.Hkv = p.Hkv;
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.S = plan.splits;
     a.c = scale * 1.4426950408889634f;
     a.causal = (p.flags & FDD_ATTN_CAUSAL_BLOCK) ? 1 : 0;
     if (plan.mtile_rows != RT) return hipErrorInvalidValue;
-    const dim3 grid(plan.MT, plan.splits, p.Hkv);
+    const dim3 grid(plan.MT, plan.splits, p.Hkv * a.batch);
     if (p.D == 128) hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(THREADS), 0, s, a);
     else hipLaunchKernelGGL(attn_f32_kernel<64>, grid, dim3(THREADS), 0, s, a);
     return hipGetLastError();
@@ -347,7 +365,9 @@ hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, f
     a.ws_o = static_cast<const float*>(p.workspace);
     a.ws_ml = reinterpret_cast<const float*>(static_cast<const char*>(p.workspace) + plan.ws_o_bytes);
     a.out = p.out;
-    a.Hq = p.Hq; a.G = plan.G; a.R = plan.R; a.MT = plan.MT;
+    const int batch = p.batch > 1 ? p.batch : 1;
+    a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = plan.G; a.R = plan.R; a.MT = plan.MT;
+    a.o_bs = p.out_batch_stride;
     a.mrows = plan.mtile_rows; a.D = p.D; a.bf16 = (p.dtype == FDD_BF16);
     a.max_seg = plan.max_seg;
     a.fixed_seg = a.bf16 ? plan.uniform : plan.splits;
@@ -356,7 +376,7 @@ hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, f
     a.rem = a.bf16 ? (int)(plan.U % plan.W) : 0;
     a.c = scale * 1.4426950408889634f;
     // more threads per row when the rows are few and the segments many
-    const long long rows = (long long)p.Hkv * plan.R;
+    const long long rows = (long long)p.Hkv * batch * plan.R;
     const int seg_hint = a.fixed_seg > 0 ? a.fixed_seg : plan.max_seg;
     int sg = 1;
     while (sg < 8 && sg * 2 <= seg_hint && rows * sg < 16384) sg *= 2;
@@ -365,7 +385,7 @@ hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, f
     const size_t smem = (size_t)((2 * a.RB * plan.max_seg + 3) & ~3) * sizeof(float) + (size_t)a.RB * sg * (p.D / 4) * sizeof(float4) +
                         (size_t)a.RB * sg * sizeof(float);
     if (smem > 60 * 1024) return hipErrorInvalidValue;
-    const dim3 grid(p.Hkv * plan.MT, (plan.mtile_rows + a.RB - 1) / a.RB);
+    const dim3 grid(p.Hkv * batch * plan.MT, (plan.mtile_rows + a.RB - 1) / a.RB);
     hipLaunchKernelGGL(attn_combine_kernel, grid, dim3(256), smem, s, a);
     return hipGetLastError();
 }

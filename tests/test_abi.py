@@ -150,6 +150,14 @@ def test_extension_and_commit_errors(lib):
                      (dict(E=8, ext_capacity=1 << 30, ext_k=2048, ext_v=2304), 2)]:
         assert lib.fdd_block_attn(C.byref(attn(**kw))) == code, kw
         assert lib.fdd_last_error().decode().startswith("fdd_block_attn:")
+    # a batch of problems: strides must cover one problem and keep 16-byte alignment
+    ok = dict(batch=3, q_batch_stride=1 * 32 * 28 * 128, out_batch_stride=1 * 32 * 28 * 128,
+              block_batch_stride=1 * 32 * 4 * 128, prefix_batch_stride=2048 * 4 * 128)
+    assert lib.fdd_block_attn_workspace(C.byref(attn(**ok))) > 0
+    for kw, code in [(dict(ok, q_batch_stride=100), 2), (dict(ok, prefix_batch_stride=2048 * 4 * 128 + 4), 2),
+                     (dict(ok, batch=-1), 2), (dict(ok, batch=20000), 2), (dict(ok, reserved=1), 4),
+                     (dict(ok, prefix_v_packed=8192, packed_batch_stride=100), 2)]:
+        assert lib.fdd_block_attn(C.byref(attn(**kw))) == code, kw
     # E = 0 ignores the extension pointers
     assert lib.fdd_block_attn_workspace(C.byref(attn(E=0, ext_capacity=64, ext_k=2048, ext_v=2304))) == \
         lib.fdd_block_attn_workspace(C.byref(attn()))

@@ -117,3 +117,40 @@ def test_three_block_lifecycle_after_a_fork(F, oracle):
             torch.cuda.synchronize()
             assert np.array_equal(ek.view(torch.int16).cpu().numpy().view(np.uint16), ek_h)
     assert E == 2 * B
+
+
+@pytest.mark.parametrize("dtype", [W.BF16, W.F32])
+@pytest.mark.parametrize("shape", [(3, 1, 32, 2048, 28, 4, 128, 0), (5, 2, 8, 333, 4, 1, 64, 8), (28, 1, 32, 256, 28, 4, 128, 0),
+                                   (2, 9, 32, 1000, 28, 4, 128, 32)])
+def test_batch_of_independent_problems(F, oracle, shape, dtype):
+    # P problems of one shape in one launch: each must match the oracle on its own arrays, with and
+    # without a prefix V laid out beforehand, and nothing may leak between problems
+    P, N, B, L, Hq, Hkv, D, E = shape
+    if dtype == W.F32 and P * N * B * Hq * (L + B) > 2e7:
+        pytest.skip("fp32 path is for small exactness checks")
+    print_case(test="batched_attn", shape=shape, dtype=dtype)
+    rng = np.random.default_rng(hash(shape) % 2**32 + 17)
+    probs = [rand_attn(rng, N, B, L, Hq, Hkv, D, dtype) for _ in range(P)]
+    exts = [rand_ext(rng, N, max(E, 1), Hkv, D, dtype) for _ in range(P)]
+    stack = lambda k: to_dev(np.stack([pr[k] for pr in probs]))
+    q, pk, pv, bk, bv = (stack(k) for k in ("q", "prefix_k", "prefix_v", "block_k", "block_v"))
+    ek, ev = to_dev(np.stack([e[0] for e in exts])), to_dev(np.stack([e[1] for e in exts]))
+    kw = dict(ext_k=ek, ext_v=ev, E=E) if E else {}
+    out = F.fdd_block_attn_batched(q, pk, pv, bk, bv, **kw)
+    outs = [out]
+    if dtype == W.BF16 and L >= 64:
+        packed = torch.stack([F.fdd_prefix_pack(pv[i]) for i in range(P)])
+        outs.append(F.fdd_block_attn_batched(q, pk, pv, bk, bv, prefix_v_packed=packed, **kw))
+    torch.cuda.synchronize()
+    for o in outs:
+        for i in range(P):
+            okw = dict(ext_k=exts[i][0], ext_v=exts[i][1], E=E) if E else {}
+            ref = oracle.block_attn(probs[i]["q"], probs[i]["prefix_k"], probs[i]["prefix_v"], probs[i]["block_k"],
+                                    probs[i]["block_v"], **okw)
+            err = np.abs(to_f64(o[i]) - ref).max()
+            assert err <= TOL[dtype], f"problem {i}: max-abs error {err}"
+    # a change in one problem's prefix moves that problem's output only
+    pk2 = pk.clone()
+    pk2[P - 1] = pk2[P - 1] * 0.5
+    out2 = F.fdd_block_attn_batched(q, pk2, pv, bk, bv, **kw)
+    assert torch.equal(out2[: P - 1], out[: P - 1]) and not torch.equal(out2[P - 1], out[P - 1])
