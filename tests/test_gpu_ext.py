@@ -154,3 +154,39 @@ def test_batch_of_independent_problems(F, oracle, shape, dtype):
     pk2[P - 1] = pk2[P - 1] * 0.5
     out2 = F.fdd_block_attn_batched(q, pk2, pv, bk, bv, **kw)
     assert torch.equal(out2[: P - 1], out[: P - 1]) and not torch.equal(out2[P - 1], out[P - 1])
+
+
+def test_seeded_random_shapes_and_options(F, oracle):
+    # a sweep of small seeded shapes over every option of the attention call at once
+    # (storage type, head size, GQA ratio, ragged L, B across tile borders, extension, causal, split count)
+    rng = np.random.default_rng(2024)
+    worst = 0.0
+    for case in range(48):
+        dtype = W.BF16 if case % 3 else W.F32
+        D = int(rng.choice([64, 128]))
+        Hkv = int(rng.choice([1, 2, 4]))
+        G = int(rng.choice([1, 3, 7]))
+        N = int(rng.integers(1, 12))
+        B = int(rng.choice([1, 5, 16, 32, 40, 64, 65, 100]))
+        L = int(rng.choice([0, 1, 63, 64, 65, 200, 777, 1024, 1500]))
+        E = int(rng.choice([0, 0, 7, 64, 90]))
+        Ecap = E + int(rng.integers(0, 9))
+        causal = bool(rng.integers(0, 2))
+        splits = int(rng.choice([0, 0, 1, 2, 5]))
+        if dtype == W.F32 and N * B * Hkv * G * (L + E + B) > 2e6:
+            N, L = min(N, 3), min(L, 200)
+        print_case(test="random_shape", case=case, dtype=dtype, N=N, B=B, L=L, Hq=Hkv * G, Hkv=Hkv, D=D, E=E, causal=causal,
+                   splits=splits)
+        d = rand_attn(rng, N, B, L, Hkv * G, Hkv, D, dtype)
+        ek, ev = rand_ext(rng, N, max(Ecap, 1), Hkv, D, dtype)
+        t = {k: to_dev(v) for k, v in d.items()}
+        kw = dict(ext_k=to_dev(ek), ext_v=to_dev(ev), E=E) if E else {}
+        out = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"], causal_block=causal,
+                               splits=splits, **kw)
+        torch.cuda.synchronize()
+        okw = dict(ext_k=ek, ext_v=ev, E=E) if E else {}
+        ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"], causal_block=causal, **okw)
+        err = np.abs(to_f64(out) - ref).max()
+        assert err <= TOL[dtype], f"case {case}: max-abs error {err}"
+        worst = max(worst, err / TOL[dtype])
+    print(f"worst error / tolerance: {worst:.3f}")
