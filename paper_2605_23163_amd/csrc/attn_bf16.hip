@@ -553,9 +553,13 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                     float pr[4];
 #pragma unroll
                     for (int t = 0; t < 4; ++t) pr[t] = fast_exp2(fmaf(s_cur[kb][4 * e + t], a.c, -mc));
-                    acc += (pr[0] + pr[1]) + (pr[2] + pr[3]);
                     typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
                     bf16x2 lo = {(__bf16)pr[0], (__bf16)pr[1]}, hi = {(__bf16)pr[2], (__bf16)pr[3]};
+                    // the row sum is taken over the probabilities as they enter P V (rounded to bf16):
+                    // numerator and denominator then see the same values, and a pair costs one instruction
+                    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+                    acc = __builtin_amdgcn_fdot2_f32_bf16(lo, ones, acc, false);
+                    acc = __builtin_amdgcn_fdot2_f32_bf16(hi, ones, acc, false);
                     uint32_t ulo = __builtin_bit_cast(uint32_t, lo), uhi = __builtin_bit_cast(uint32_t, hi);
                     FDD_PIN(ulo);
                     FDD_PIN(uhi);
