@@ -473,6 +473,7 @@ def main():
                    "N": w.N, "B": w.B, "L": w.L, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "V": w.V,
                    "scaffold_frac": w.scaffold_frac, "tau": w.tau},
         "wall_ms_per_step": round(wall * 1e3 / args.steps, 4),
+        "ms_per_block_of_8_steps": round(ms_step * STEPS_PER_BLOCK, 4),
         "roofline": {"kernel": "attn_bf16_kernel", "bound": "mfma", "achieved": round(flops / (attn_ms * 1e-3) / 1e12, 2),
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
@@ -502,6 +503,7 @@ def main():
     if not args.no_supplements:
         n1 = W.CONFIGS["cfg2"]
         res["n1_prefix_stream"] = time_attention_only(F, n1, 400, 40, 128)
+        res["n1_prefix_stream_warm"] = time_attention_only(F, n1, 200, 20, 1)      # one buffer: served from the caches
         n1_long = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
         res["n1_prefix_stream_L16384"] = time_attention_only(F, n1_long, 200, 20, 20)
         res["n1_layer_sweep"] = time_layer_sweep_graph(F, n1, 28, 20)
