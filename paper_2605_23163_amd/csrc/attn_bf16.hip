@@ -113,6 +113,8 @@ struct Args {
     int base, rem;  // free ranges: U / W and U % W
     int causal;     // in-block keys are visible up to the query's own position only
     float c;        // scale * log2(e)
+    int ttpr;       // private tiles per rollout: extension tiles, then block tiles
+    FastDiv dMT, dS, dTPU, dHkv, dG, dB, dBG, dTTPR, dBase, dBase1;   // divisions by launch constants
 };
 
 template <int D, int WAVES>
@@ -192,15 +194,16 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     if (a.S > 0) {
         // equal pieces: neighbours are the M-tiles of one (KV head, piece), which
         // walk the same keys in step, so each XCD fetches its share of K/V once
-        const int mt_ = wg % a.MT, rest = wg / a.MT;
-        piece = rest % a.S;
-        M = (rest / a.S) * a.MT + mt_;
-        t_begin = a.TPU * piece / a.S;
-        todo = a.TPU * (piece + 1) / a.S - t_begin;
+        const int rest = fast_div(wg, a.dMT), mt_ = wg - rest * a.MT;
+        const int khv_ = fast_div(rest, a.dS);
+        piece = rest - khv_ * a.S;
+        M = khv_ * a.MT + mt_;
+        t_begin = fast_div(a.TPU * piece, a.dS);
+        todo = fast_div(a.TPU * (piece + 1), a.dS) - t_begin;
     } else {
         const int u0 = unit_begin(wg, a.base, a.rem);
         todo = unit_begin(wg + 1, a.base, a.rem) - u0;
-        M = u0 / a.TPU;
+        M = fast_div(u0, a.dTPU);
         t_begin = u0 - M * a.TPU;
     }
 
@@ -264,9 +267,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const int t_end = min(a.TPU, t_begin + todo);
         todo -= t_end - t_begin;
         // M runs over (problem of the batch, KV head, M-tile)
-        const int khv = M / a.MT;
+        const int khv = fast_div(M, a.dMT);
         const int mt = M - khv * a.MT;
-        const int pb = a.batch > 1 ? khv / a.Hkv : 0;
+        const int pb = a.batch > 1 ? fast_div(khv, a.dHkv) : 0;
         const int kh = khv - pb * a.Hkv;
         // (the arrays of problem pb are addressed where they are used: few of these pointers are live at a time)
         const __amdgpu_buffer_rsrc_t pk_rsrc = __builtin_amdgcn_make_buffer_rsrc(
@@ -321,7 +324,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const int row0 = row0_wg + wave * 32;
         const int row = row0 + l32;
         const bool row_ok = row < a.R;
-        const int nb = row_ok ? row / a.G : 0;           // n*B + b
+        const int nb = row_ok ? fast_div(row, a.dG) : 0;           // n*B + b
         const int g = row_ok ? row - nb * a.G : 0;
         bf16x8 qf[KS];
         {
@@ -341,21 +344,23 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             n_seg = a.S;
             seg = piece;
         } else {
-            const int first = wg_of_unit(M * a.TPU, a.base, a.rem);
-            n_seg = wg_of_unit((M + 1) * a.TPU - 1, a.base, a.rem) - first + 1;
+            // owner of a unit: the first `rem` workgroups hold base + 1 units each, the others base
+            const int cut = a.rem * (a.base + 1);
+            auto owner = [&](int u) { return u < cut ? fast_div(u, a.dBase1) : a.rem + fast_div(u - cut, a.dBase); };
+            const int first = owner(M * a.TPU);
+            n_seg = owner((M + 1) * a.TPU - 1) - first + 1;
             seg = wg - first;
         }
-        const int BG = a.B * a.G;
-        const int my_rollout = row_ok ? nb / a.B : -1;
+        const int my_rollout = row_ok ? fast_div(nb, a.dB) : -1;
         const int my_b = row_ok ? nb - my_rollout * a.B : 0;   // position inside the block
         // rollouts spanned by this wave's rows and by the whole M-tile
-        const int wave_n_lo = row0 / BG;
-        const int wave_n_hi = (min(row0 + 31, a.R - 1)) / BG;
+        const int wave_n_lo = fast_div(row0, a.dBG);
+        const int wave_n_hi = fast_div(min(row0 + 31, a.R - 1), a.dBG);
         const bool wave_has_rows = row0 < a.R;
-        const int wg_n_lo = __builtin_amdgcn_readfirstlane(row0_wg / BG);
-        const int wg_n_hi = __builtin_amdgcn_readfirstlane((min(row0_wg + MROWS - 1, a.R - 1)) / BG);
-        const int tte = (a.E + KT - 1) / KT;             // tiles of a rollout's extension
-        const int ttpr = tte + (a.B + KT - 1) / KT;      // private tiles per rollout: extension, then block
+        const int wg_n_lo = __builtin_amdgcn_readfirstlane(fast_div(row0_wg, a.dBG));
+        const int wg_n_hi = __builtin_amdgcn_readfirstlane(fast_div(min(row0_wg + MROWS - 1, a.R - 1), a.dBG));
+        const int tte = (a.E + KT - 1) >> 6;             // tiles of a rollout's extension
+        const int ttpr = a.ttpr;                         // private tiles per rollout: extension, then block
         const int n_tail = (t_end == a.TPU) ? (wg_n_hi - wg_n_lo + 1) * ttpr : 0;
         const int n_tiles = n_prefix + n_tail;
 
@@ -378,8 +383,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                 const int jj = j - n_prefix;
                 int n = wg_n_lo + jj, w = 0;
                 if (ttpr > 1) {
-                    n = wg_n_lo + jj / ttpr;
-                    w = jj % ttpr;
+                    const int q_ = fast_div(jj, a.dTTPR);
+                    n = wg_n_lo + q_;
+                    w = jj - q_ * ttpr;
                 }
                 t.rollout = n;
                 if (w < tte) {
@@ -835,6 +841,17 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.base = (int)(plan.U / plan.W); a.rem = (int)(plan.U % plan.W);
     a.causal = (p.flags & FDD_ATTN_CAUSAL_BLOCK) ? 1 : 0;
     a.c = scale * 1.4426950408889634f;
+    a.ttpr = (p.E + 63) / 64 + (p.B + 63) / 64;
+    a.dMT = make_fastdiv((uint32_t)a.MT);
+    a.dS = make_fastdiv((uint32_t)(a.S > 0 ? a.S : 1));
+    a.dTPU = make_fastdiv((uint32_t)a.TPU);
+    a.dHkv = make_fastdiv((uint32_t)a.Hkv);
+    a.dG = make_fastdiv((uint32_t)a.G);
+    a.dB = make_fastdiv((uint32_t)a.B);
+    a.dBG = make_fastdiv((uint32_t)(a.B * a.G));
+    a.dTTPR = make_fastdiv((uint32_t)a.ttpr);
+    a.dBase = make_fastdiv((uint32_t)(a.base > 0 ? a.base : 1));
+    a.dBase1 = make_fastdiv((uint32_t)(a.base + 1));
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;
     if (plan.packed)
         return p.D == 128 ? launch<128, 8, true>(a, pack_now, s, before_main) : launch<64, 8, true>(a, pack_now, s, before_main);

@@ -49,6 +49,29 @@ struct AttnPlan {
 
 bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan);
 
+// Division by a number fixed per launch, prepared on the host: for 0 <= n < 2^31 and 1 <= d < 2^31,
+// n / d = ((n + 1) * mul) >> (32 + shift), where k = 31 + max(1, ceil(log2 d)), shift = k - 32 and mul is the
+// largest integer with mul * d < 2^k.  With e = 2^k - mul * d in (0, d] and n = q d + r the product is
+// q + ((r + 1) - (n + 1) e / 2^k) / d, and (n + 1) e <= 2^k keeps the bracket in [r, r + 1).
+struct FastDiv {
+    uint32_t mul, shift;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    if (d == 0) d = 1;   // never used as a divisor then; keeps the host arithmetic defined
+    uint32_t s = 1;
+    while ((1ull << s) < d) ++s;
+    const uint64_t two_k = 1ull << (31 + s);
+    FastDiv f;
+    f.mul = (uint32_t)((two_k - 1) / d);
+    f.shift = s - 1;
+    return f;
+}
+__device__ __forceinline__ int fast_div(int n, const FastDiv& f)
+{
+    return (int)((uint32_t)(((uint64_t)((uint32_t)n + 1u) * f.mul) >> 32) >> f.shift);
+}
+
 // Stream-K ranges: U units over W workgroups, base = U / W, rem = U % W; the
 // first `rem` workgroups own base + 1 units, the others base (>= 1).
 __host__ __device__ inline int unit_begin(int w, int base, int rem) { return w * base + (w < rem ? w : rem); }
