@@ -335,6 +335,33 @@ def time_extension(F, w, d, g, steps, warmup):
             "commit_bytes": 4 * w.N * w.B * w.Hkv * w.D * 2}
 
 
+def time_scaffold_skip(F, w, d, g, steps, warmup):
+    """The last layer of a step: only non-scaffold positions need an output row."""
+    import torch
+    import fdd_workloads as W
+    st = {k: dev(d[k]) for k in ("block_k", "block_v")}
+    scaffold = W.scaffold_positions(w, np.random.default_rng(w.seed))
+    pos = torch.from_numpy(np.flatnonzero(scaffold.reshape(-1) == 0).astype(np.int32)).cuda()
+    out = torch.zeros_like(g["q"])
+    packed_v = F.fdd_prefix_pack(g["prefix_v"])
+    ws = torch.empty(max(256, F.fdd_block_attn_workspace(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"],
+                                                         prefix_v_packed=packed_v, n_q_positions=pos.numel())),
+                     dtype=torch.uint8, device="cuda")
+    ev = Events(steps)
+    for i in range(warmup + steps):
+        if i >= warmup:
+            F.fdd_profile_attn_events(*ev.pairs[i - warmup])
+        F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"], out=out, workspace=ws,
+                         prefix_v_packed=packed_v, q_positions=pos)
+    torch.cuda.synchronize()
+    F.fdd_profile_attn_events(None, None)
+    ms = ev.mean_ms(steps)
+    flops = 4.0 * pos.numel() * w.Hq * (w.L + w.B) * w.D
+    return {"workload": f"{w.name}, query rows of the {pos.numel()} non-scaffold positions of {w.N * w.B}",
+            "attn_kernel_us": round(ms * 1e3, 2), "attn_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+            "attn_frac_peak_mfma": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4)}
+
+
 def cpu_baseline(w, d, logits):
     """The fp64 oracle as it stands on a bounded sample of one step."""
     import oracle
@@ -513,6 +540,7 @@ def main():
         if has_unmask:
             res["spec_verify"] = time_spec_verify(F, w, d, g, logits, 100, 10)
         res["extension_block"] = time_extension(F, w, d, g, 50, 5)
+        res["scaffold_skip"] = time_scaffold_skip(F, w, d, g, 50, 5)
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, d, logits_h)
     print(json.dumps(res))

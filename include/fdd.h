@@ -117,9 +117,18 @@ typedef struct fdd_attn_params {
      * i*packed_batch_stride (bytes, a multiple of 256).  batch <= 1 is the single problem and the strides
      * are ignored.  Nothing is shared between the problems of a batch. */
     int32_t batch;
-    int32_t reserved;              /* must be 0 */
+    int32_t n_q_positions;         /* 0: every position is computed; see q_positions */
     int64_t q_batch_stride, prefix_batch_stride, block_batch_stride, ext_batch_stride, out_batch_stride;
     size_t packed_batch_stride;
+    /* Only some block positions as queries ("Scaffold": scaffold tokens are given, never predicted, so
+     * where nothing but the logits of a layer's output is read - the last layer - their rows are not
+     * needed).  q_positions is a DEVICE array of n_q_positions flat positions n*B + b in strictly ascending
+     * order, each in [0, N*B); the rows out[n, b, :, :] of these positions are computed exactly as without
+     * the list, every other row of `out` is left as it was.  Keys are not affected: block_k / block_v
+     * still hold all B positions of every rollout.  With `batch`, the one list serves every problem.
+     * The library cannot read the list on the host: entries out of range are clamped into it by the
+     * kernels (no access out of bounds), an order other than ascending gives undefined values in `out`. */
+    const int32_t *q_positions;
 } fdd_attn_params;
 
 /* Bytes of scratch fdd_block_attn needs for these params (host-only

@@ -34,9 +34,10 @@ class AttnParams(C.Structure):
                 ("out", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
                 ("stream", C.c_void_p), ("splits", C.c_int32), ("flags", C.c_int32),
                 ("prefix_v_packed", C.c_void_p), ("ext_k", C.c_void_p), ("ext_v", C.c_void_p),
-                ("E", C.c_int32), ("ext_capacity", C.c_int32), ("batch", C.c_int32), ("reserved", C.c_int32),
+                ("E", C.c_int32), ("ext_capacity", C.c_int32), ("batch", C.c_int32), ("n_q_positions", C.c_int32),
                 ("q_batch_stride", C.c_int64), ("prefix_batch_stride", C.c_int64), ("block_batch_stride", C.c_int64),
-                ("ext_batch_stride", C.c_int64), ("out_batch_stride", C.c_int64), ("packed_batch_stride", C.c_size_t)]
+                ("ext_batch_stride", C.c_int64), ("out_batch_stride", C.c_int64), ("packed_batch_stride", C.c_size_t),
+                ("q_positions", C.c_void_p)]
 
 
 class UnmaskParams(C.Structure):
@@ -228,26 +229,35 @@ def fdd_prefix_pack(prefix_v, packed=None, stream=None):
 
 
 def fdd_block_attn_workspace(q, prefix_k, prefix_v, block_k, block_v, splits=0, prefix_v_packed=None,
-                             ext_k=None, ext_v=None, E=0) -> int:
-    """Workspace bytes of the fdd_block_attn call with these arguments (E counts: the work split depends on it)."""
+                             ext_k=None, ext_v=None, E=0, n_q_positions=0) -> int:
+    """Workspace bytes of the fdd_block_attn call with these arguments (E and the number of query
+    positions count: the work split depends on them)."""
     p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, None, None, None, splits, prefix_v_packed, False,
                      ext_k, ext_v, E)
+    p.n_q_positions = int(n_q_positions)
     return load_library().fdd_block_attn_workspace(C.byref(p))
 
 
 def fdd_block_attn(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask=None, out=None, scale=None,
                    workspace=None, stream=None, splits=0, prefix_v_packed=None, causal_block=False,
-                   ext_k=None, ext_v=None, E=0):
+                   ext_k=None, ext_v=None, E=0, q_positions=None):
     """out[N,B,Hq,D] = shared-prefix block-causal attention (see include/fdd.h).
     ``causal_block=True`` is the verify pass: causal inside the block.
     ``ext_k/ext_v`` [N,ext_capacity,Hkv,D] with ``E`` valid rows: the blocks each
-    rollout has committed since the fork."""
+    rollout has committed since the fork.
+    ``q_positions``: int32 device tensor of ascending flat positions n*B+b; only
+    their rows of ``out`` are written (pass ``out`` then)."""
     import torch
     lib = load_library()
     if out is None:
         out = torch.empty_like(q)
     p = _attn_params(q, prefix_k, prefix_v, block_k, block_v, scaffold_mask, out, scale, splits, prefix_v_packed,
                      causal_block, ext_k, ext_v, E)
+    if q_positions is not None:
+        if q_positions.dtype != torch.int32 or q_positions.dim() != 1 or not q_positions.is_contiguous():
+            raise ValueError("q_positions must be a contiguous 1-D int32 tensor")
+        p.q_positions = _dev(q_positions, "q_positions")
+        p.n_q_positions = q_positions.numel()
     need = lib.fdd_block_attn_workspace(C.byref(p))
     ws, nbytes = _workspace(workspace, need, q.device)
     p.workspace = ws.data_ptr() if ws is not None else None

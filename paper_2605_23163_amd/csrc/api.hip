@@ -4,6 +4,7 @@
 #include <cstdio>
 
 #include "fdd_internal.h"
+#include <algorithm>
 
 namespace fdd {
 namespace {
@@ -48,7 +49,8 @@ fdd_status check_attn_shape(const fdd_attn_params* p)
     }
     if (std::isnan(p->scale) || std::isinf(p->scale)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: scale is not finite");
     if (p->batch < 0 || p->batch > 65535 / p->Hkv) return fail(FDD_ERR_SHAPE, "fdd_block_attn: batch=%d outside [0, 65535 / Hkv]", p->batch);
-    if (p->reserved != 0) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: reserved field must be 0");
+    if (p->n_q_positions < 0 || (long long)p->n_q_positions > (long long)p->N * p->B)
+        return fail(FDD_ERR_SHAPE, "fdd_block_attn: n_q_positions=%d outside [0, N*B]", p->n_q_positions);
     if (p->batch > 1) {
         const long long es = p->dtype == FDD_BF16 ? 2 : 4;
         struct { const char* name; long long stride, need; } st[] = {
@@ -79,7 +81,7 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
 {
     AttnPlan pl;
     pl.G = p.Hq / p.Hkv;
-    pl.R = p.N * p.B * pl.G;
+    pl.R = (p.n_q_positions > 0 ? p.n_q_positions : p.N * p.B) * pl.G;
     if (p.dtype == FDD_BF16) {
         pl.mtile_rows = 256;
         pl.key_tile = 64;
@@ -97,7 +99,8 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
         // by the workgroup that ends the M-tile's key range, one after the other and at about 1.8 times the
         // cost of a pipelined prefix tile.  They are booked as `wt` extra units at the end of the M-tile's
         // unit range, so that this workgroup gets correspondingly fewer prefix tiles.
-        const long long BG = (long long)p.B * pl.G;
+        // (with a list of query positions a rollout contributes fewer rows: its average share stands in for B)
+        const long long BG = p.n_q_positions > 0 ? std::max(1ll, (long long)p.n_q_positions * pl.G / p.N) : (long long)p.B * pl.G;
         const long long span_lo = (pl.mtile_rows + BG - 1) / BG;                 // rollouts an M-tile spans at least
         const long long span = span_lo + ((pl.mtile_rows % BG) != 0 && BG < (long long)pl.R ? 1 : 0);
         const long long private_tiles = (span < p.N ? span : p.N) *
@@ -213,6 +216,8 @@ fdd_status fdd_block_attn(const fdd_attn_params* p)
     if (!p->q || !p->block_k || !p->block_v || !p->out) return fail(FDD_ERR_NULL, "fdd_block_attn: q, block_k, block_v and out must not be NULL");
     if (p->L > 0 && (!p->prefix_k || !p->prefix_v)) return fail(FDD_ERR_NULL, "fdd_block_attn: prefix_k / prefix_v is NULL with L=%d", p->L);
     if (p->E > 0 && (!p->ext_k || !p->ext_v)) return fail(FDD_ERR_NULL, "fdd_block_attn: ext_k / ext_v is NULL with E=%d", p->E);
+    if (p->n_q_positions > 0 && !p->q_positions) return fail(FDD_ERR_NULL, "fdd_block_attn: q_positions is NULL with n_q_positions=%d", p->n_q_positions);
+    if (p->n_q_positions > 0 && (reinterpret_cast<uintptr_t>(p->q_positions) & 3u)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: q_positions must be 4-byte aligned");
     const void* ptrs[] = {p->q, p->prefix_k, p->prefix_v, p->block_k, p->block_v, p->out, p->prefix_v_packed,
                           p->E > 0 ? p->ext_k : nullptr, p->E > 0 ? p->ext_v : nullptr};
     for (const void* x : ptrs)

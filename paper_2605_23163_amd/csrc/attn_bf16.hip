@@ -114,6 +114,8 @@ struct Args {
     int causal;     // in-block keys are visible up to the query's own position only
     float c;        // scale * log2(e)
     int ttpr;       // private tiles per rollout: extension tiles, then block tiles
+    const int32_t* qpos;   // stacked rows are the listed block positions only (ascending n*B + b), or nullptr: all of them
+    int NB;         // N * B
     FastDiv dMT, dS, dTPU, dHkv, dG, dB, dBG, dTTPR, dBase, dBase1;   // divisions by launch constants
 };
 
@@ -324,8 +326,10 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const int row0 = row0_wg + wave * 32;
         const int row = row0 + l32;
         const bool row_ok = row < a.R;
-        const int nb = row_ok ? fast_div(row, a.dG) : 0;           // n*B + b
-        const int g = row_ok ? row - nb * a.G : 0;
+        // a stacked row is (entry of the list of query positions, query head of the group)
+        const int sel = row_ok ? fast_div(row, a.dG) : 0;
+        const int g = row_ok ? row - sel * a.G : 0;
+        const int nb = a.qpos ? min(max(a.qpos[sel], 0), a.NB - 1) : sel;   // n*B + b
         bf16x8 qf[KS];
         {
             const uint16_t* qp = a.q + pb * a.q_bs + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D + half * 8;
@@ -354,11 +358,18 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const int my_rollout = row_ok ? fast_div(nb, a.dB) : -1;
         const int my_b = row_ok ? nb - my_rollout * a.B : 0;   // position inside the block
         // rollouts spanned by this wave's rows and by the whole M-tile
-        const int wave_n_lo = fast_div(row0, a.dBG);
-        const int wave_n_hi = fast_div(min(row0 + 31, a.R - 1), a.dBG);
+        // (rows are in ascending order of position, hence of rollout; `r` is clamped to the rows that exist)
+        auto rollout_of_row = [&](int r) {
+            r = min(r, a.R - 1);
+            if (!a.qpos) return fast_div(r, a.dBG);
+            const int e = __builtin_amdgcn_readfirstlane(fast_div(r, a.dG));
+            return fast_div(min(max(a.qpos[e], 0), a.NB - 1), a.dB);
+        };
+        const int wave_n_lo = rollout_of_row(row0);
+        const int wave_n_hi = rollout_of_row(row0 + 31);
         const bool wave_has_rows = row0 < a.R;
-        const int wg_n_lo = __builtin_amdgcn_readfirstlane(fast_div(row0_wg, a.dBG));
-        const int wg_n_hi = __builtin_amdgcn_readfirstlane(fast_div(min(row0_wg + MROWS - 1, a.R - 1), a.dBG));
+        const int wg_n_lo = __builtin_amdgcn_readfirstlane(rollout_of_row(row0_wg));
+        const int wg_n_hi = __builtin_amdgcn_readfirstlane(rollout_of_row(row0_wg + MROWS - 1));
         const int tte = (a.E + KT - 1) >> 6;             // tiles of a rollout's extension
         const int ttpr = a.ttpr;                         // private tiles per rollout: extension, then block
         const int n_tail = (t_end == a.TPU) ? (wg_n_hi - wg_n_lo + 1) * ttpr : 0;
@@ -842,6 +853,8 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.causal = (p.flags & FDD_ATTN_CAUSAL_BLOCK) ? 1 : 0;
     a.c = scale * 1.4426950408889634f;
     a.ttpr = (p.E + 63) / 64 + (p.B + 63) / 64;
+    a.qpos = p.n_q_positions > 0 ? p.q_positions : nullptr;
+    a.NB = p.N * p.B;
     a.dMT = make_fastdiv((uint32_t)a.MT);
     a.dS = make_fastdiv((uint32_t)(a.S > 0 ? a.S : 1));
     a.dTPU = make_fastdiv((uint32_t)a.TPU);

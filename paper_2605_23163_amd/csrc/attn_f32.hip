@@ -33,7 +33,14 @@ struct Args {
     int N, B, L, Hq, Hkv, G, R, MT, TP, S;
     int causal;   // in-block keys are visible up to the query's own position only
     float c;   // scale * log2(e)
+    const int32_t* qpos;   // stacked rows are the listed block positions only (ascending n*B + b), or nullptr: all of them
 };
+
+// block position n*B + b of entry `e` of the list of query positions (clamped into range), or e itself without a list
+__device__ __forceinline__ int position_of(const int32_t* qpos, int e, int NB)
+{
+    return qpos ? min(max(qpos[e], 0), NB - 1) : e;
+}
 
 template <int D>
 __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
@@ -66,13 +73,15 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
     const int sub = tid % 16;           // 16 threads cooperate on a row
     const int row = mt * RT + r_loc;
     const bool row_ok = row < a.R;
-    const int nb = row_ok ? row / a.G : 0;
+    const int NB = a.N * a.B;
+    const int nb = row_ok ? position_of(a.qpos, row / a.G, NB) : 0;
     const int g = row_ok ? row % a.G : 0;
     const int my_rollout = row_ok ? nb / a.B : -1;
     const int my_b = row_ok ? nb % a.B : 0;
+    // (rows are in ascending order of position, hence of rollout)
     const int wg_row_hi = min(mt * RT + RT - 1, a.R - 1);
-    const int wg_n_lo = (mt * RT) / BG;
-    const int wg_n_hi = wg_row_hi / BG;
+    const int wg_n_lo = a.qpos ? position_of(a.qpos, (mt * RT) / a.G, NB) / a.B : (mt * RT) / BG;
+    const int wg_n_hi = a.qpos ? position_of(a.qpos, wg_row_hi / a.G, NB) / a.B : wg_row_hi / BG;
 
     // stage the query rows
     for (int i = tid; i < RT * (D / 4); i += THREADS) {
@@ -80,7 +89,7 @@ __global__ __launch_bounds__(THREADS) void attn_f32_kernel(Args a)
         const int rr = mt * RT + r;
         float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
         if (rr < a.R) {
-            const int nb_ = rr / a.G, g_ = rr % a.G;
+            const int nb_ = position_of(a.qpos, rr / a.G, NB), g_ = rr % a.G;
             x = *reinterpret_cast<const float4*>(a.q + ((size_t)nb_ * a.Hq + (size_t)kh * a.G + g_) * D + c4 * 4);
         }
         *reinterpret_cast<float4*>(&qs[r * DP + c4 * 4]) = x;
@@ -224,6 +233,8 @@ struct CombineArgs {
     int SG;          // segment groups: the segments of a row are shared out over SG threads per channel quad
     int RB;          // rows per block; RB * SG * D/4 = 256 threads
     float c;
+    const int32_t* qpos;   // list of query positions, as in the attention kernels, or nullptr
+    int NB;                // N * B
 };
 
 // grid (Hkv*MT, ceil(mrows / RB)).  Thread (r, sg, d4) sums segments sg, sg+SG, ..
@@ -313,7 +324,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(CombineArgs a)
     }
     if (!live) return;
     const float inv = 1.f / l;
-    const int nb = row / a.G, g = row - nb * a.G;
+    const int sel = row / a.G, g = row - sel * a.G;
+    const int nb = position_of(a.qpos, sel, a.NB);
     const size_t off = (size_t)(pb * a.o_bs) + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * a.D + d4 * 4;
     if (a.bf16) {
         typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
@@ -352,6 +364,7 @@ hipError_t launch_attn_f32(const fdd_attn_params& p, const AttnPlan& plan, float
     a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.TP = plan.TP; a.S = plan.splits;
     a.c = scale * 1.4426950408889634f;
     a.causal = (p.flags & FDD_ATTN_CAUSAL_BLOCK) ? 1 : 0;
+    a.qpos = p.n_q_positions > 0 ? p.q_positions : nullptr;
     if (plan.mtile_rows != RT) return hipErrorInvalidValue;
     const dim3 grid(plan.MT, plan.splits, p.Hkv * a.batch);
     if (p.D == 128) hipLaunchKernelGGL(attn_f32_kernel<128>, grid, dim3(THREADS), 0, s, a);
@@ -368,6 +381,8 @@ hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, f
     const int batch = p.batch > 1 ? p.batch : 1;
     a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = plan.G; a.R = plan.R; a.MT = plan.MT;
     a.o_bs = p.out_batch_stride;
+    a.qpos = p.n_q_positions > 0 ? p.q_positions : nullptr;
+    a.NB = p.N * p.B;
     a.mrows = plan.mtile_rows; a.D = p.D; a.bf16 = (p.dtype == FDD_BF16);
     a.max_seg = plan.max_seg;
     a.fixed_seg = a.bf16 ? plan.uniform : plan.splits;

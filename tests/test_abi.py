@@ -155,7 +155,8 @@ def test_extension_and_commit_errors(lib):
               block_batch_stride=1 * 32 * 4 * 128, prefix_batch_stride=2048 * 4 * 128)
     assert lib.fdd_block_attn_workspace(C.byref(attn(**ok))) > 0
     for kw, code in [(dict(ok, q_batch_stride=100), 2), (dict(ok, prefix_batch_stride=2048 * 4 * 128 + 4), 2),
-                     (dict(ok, batch=-1), 2), (dict(ok, batch=20000), 2), (dict(ok, reserved=1), 4),
+                     (dict(ok, batch=-1), 2), (dict(ok, batch=20000), 2), (dict(ok, n_q_positions=1), 1),
+                     (dict(ok, n_q_positions=-1), 2), (dict(ok, n_q_positions=33), 2), (dict(ok, n_q_positions=4, q_positions=8194), 4),
                      (dict(ok, prefix_v_packed=8192, packed_batch_stride=100), 2)]:
         assert lib.fdd_block_attn(C.byref(attn(**kw))) == code, kw
     # E = 0 ignores the extension pointers
