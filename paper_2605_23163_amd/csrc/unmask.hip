@@ -73,6 +73,17 @@ struct Run {
     float s;      // sum of 2^((x - m) log2 e) over what was seen
 };
 
+// A thread's running sum takes its terms as 2^(x c - fl(m c)), c = log2 e, with one fused
+// multiply-add each.  fl(m c) is off from m c by up to half an ulp, which scales every term
+// by the same 2^(m c - fl(m c)): harmless as long as the whole sum is relative to the same
+// fl(m c).  So a new maximum rescales the sum by 2^(fl(m_old c) - fl(m_new c)), the
+// difference of the rounded products, and the common factor is taken out once, by
+// `settle`, before sums of different threads meet.
+struct ThreadRun {
+    Run r;
+    float mc;     // fl(r.m * log2 e)
+};
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // `b` is merged into `a`; on equal maxima the lower index wins.
@@ -88,26 +99,37 @@ __device__ __forceinline__ void merge(Run& a, const Run& b)
 }
 
 template <int VEC>
-__device__ __forceinline__ void absorb(Run& r, const float (&x)[VEC], int v0)
+__device__ __forceinline__ void absorb(ThreadRun& t, const float (&x)[VEC], int v0)
 {
+    Run& r = t.r;
     float cm = x[0];
 #pragma unroll
     for (int j = 1; j < VEC; ++j) cm = fmaxf(cm, x[j]);
     if (cm > r.m) {
         // this thread walks the row in ascending order, so a strictly larger
         // value is the only way its arg max can move
-        r.s *= fast_exp2((r.m - cm) * LOG2E);
+        const float mc_new = cm * LOG2E;
+        r.s *= fast_exp2(t.mc - mc_new);      // (-inf - finite at the start: the sum is still 0)
         r.m = cm;
+        t.mc = mc_new;
         int first = VEC - 1;
 #pragma unroll
         for (int j = VEC - 2; j >= 0; --j) first = (x[j] == cm) ? j : first;
         r.idx = v0 + first;
     }
-    const float mc = r.m * LOG2E;
+    const float mc = t.mc;
     float acc = 0.f;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) acc += fast_exp2(fmaf(x[j], LOG2E, -mc));
     r.s += acc;
+}
+
+// the sum as taken against m itself (see ThreadRun)
+__device__ __forceinline__ Run settle(const ThreadRun& t)
+{
+    Run r = t.r;
+    if (r.m != -INFINITY) r.s *= fast_exp2(-fmaf(r.m, LOG2E, -t.mc));
+    return r;
 }
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
@@ -126,10 +148,11 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
     const T* base = static_cast<const T*>(a.logits) + (size_t)row * (size_t)a.V;
     const int tid = threadIdx.x;
 
-    Run r;
-    r.m = -INFINITY;
-    r.idx = 0x7fffffff;
-    r.s = 0.f;
+    ThreadRun tr;
+    tr.r.m = -INFINITY;
+    tr.r.idx = 0x7fffffff;
+    tr.r.s = 0.f;
+    tr.mc = -INFINITY;
 
     if (v_lo < v_hi) {
         // leading elements up to the first 16-byte boundary, then whole
@@ -143,7 +166,7 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
 
         if (tid < head) {
             float x[1] = {sizeof(T) == 2 ? bf16_to_f32(((const uint16_t*)base)[v_lo + tid]) : ((const float*)base)[v_lo + tid]};
-            absorb<1>(r, x, (int)(v_lo + tid));
+            absorb<1>(tr, x, (int)(v_lo + tid));
         }
         const u32x4* vp = reinterpret_cast<const u32x4*>(base + body0);
         auto widen = [&](const u32x4& raw, float (&x)[VEC]) {
@@ -171,24 +194,25 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
             for (int u = 0; u < UNROLL; ++u) {
                 float x[VEC];
                 widen(raw[u], x);
-                absorb<VEC>(r, x, (int)(body0 + (i + u * RTHREADS) * VEC));
+                absorb<VEC>(tr, x, (int)(body0 + (i + u * RTHREADS) * VEC));
             }
         }
         for (; i < nvec; i += RTHREADS) {
             const u32x4 raw = __builtin_nontemporal_load(vp + i);
             float x[VEC];
             widen(raw, x);
-            absorb<VEC>(r, x, (int)(body0 + i * VEC));
+            absorb<VEC>(tr, x, (int)(body0 + i * VEC));
         }
         const long long ntail = v_hi - tail0;
         if (tid < ntail) {
             float x[1] = {sizeof(T) == 2 ? bf16_to_f32(((const uint16_t*)base)[tail0 + tid]) : ((const float*)base)[tail0 + tid]};
             // tail indices are larger than anything this thread saw before
-            absorb<1>(r, x, (int)(tail0 + tid));
+            absorb<1>(tr, x, (int)(tail0 + tid));
         }
     }
 
     // wavefront reduction, then across the 4 wavefronts through LDS
+    Run r = settle(tr);
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
         Run o;
