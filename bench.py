@@ -397,6 +397,8 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=16)
     ap.add_argument("--workload", default="cfg5", choices=["cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--event-stride", type=int, default=5,
+                    help="every this many timed steps carry the timing events the rooflines are measured with")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-supplements", action="store_true")
     ap.add_argument("--n1-only", action="store_true",
@@ -450,13 +452,22 @@ def main():
                        device="cuda")
     tau = float(np.float32(w.tau))
 
-    ev = Events(args.steps)
-    un0 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-    un1 = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    # Kernel timings for the rooflines are taken live in the timed region, on a sample of its steps: a pair
+    # of timing events costs a few microseconds of idle GPU around the kernel it brackets, so only every
+    # `stride`-th step carries the pair around the attention kernel and another one the pair around the
+    # unmask call.  The stride is odd: the samples cover the 8 steps of a block evenly.
+    stride = max(1, min(args.event_stride, args.steps // 2 if args.steps >= 2 else 1))   # both pairs get samples
+    n_samples = (args.steps + stride - 1) // stride
+    ev = Events(n_samples)
+    un0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_samples)]
+    un1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_samples)]
+    n_un = 0
 
     def step(i, timed):
-        if timed:
-            F.fdd_profile_attn_events(*ev.pairs[i])
+        nonlocal n_un
+        attn_timed = timed and i % stride == 0
+        un_timed = timed and i % stride == stride // 2
+        F.fdd_profile_attn_events(*(ev.pairs[i // stride] if attn_timed else (None, None)))
         if i % STEPS_PER_BLOCK == 0:
             # a new block: fork the rollouts and lay the (unchanged) prefix V out for the kernel once
             for k in parent:
@@ -465,11 +476,12 @@ def main():
         F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"], scaffold, out=out,
                          workspace=ws_a, prefix_v_packed=packed_v)
         if has_unmask:
-            if timed:
-                un0[i].record()
+            if un_timed:
+                un0[n_un].record()
             F.fdd_unmask_step(logits[i % 2], st["mask"], scaffold, tau, st["tokens"], conf, nun, com, workspace=ws_u)
-            if timed:
-                un1[i].record()
+            if un_timed:
+                un1[n_un].record()
+                n_un += 1
             F.fdd_block_kv_update(st["tokens"], com, tk, tv, st["block_k"], st["block_v"])
 
     for i in range(args.warmup):
@@ -486,7 +498,7 @@ def main():
     wall = time.perf_counter() - wall0
     F.fdd_profile_attn_events(None, None)
     ms_step = t0.elapsed_time(t1) / args.steps
-    attn_ms = ev.mean_ms(args.steps)
+    attn_ms = ev.mean_ms(n_samples)
     tokens_per_s = w.N * w.B / (ms_step * 1e-3)
 
     flops = attn_flops(w)
@@ -507,16 +519,17 @@ def main():
                      "traffic": (round(sum(MEASURED_TRAFFIC_MIB[w.name]["attn_bf16_kernel"]) * 2 ** 20)
                                  if w.name in MEASURED_TRAFFIC_MIB else None),
                      "algorithmic_bytes": attn_bytes(w)[1],
-                     "flops_per_launch": flops, "avg_launch_us": round(attn_ms * 1e3, 2)},
+                     "flops_per_launch": flops, "avg_launch_us": round(attn_ms * 1e3, 2),
+                     "launches_timed": n_samples, "event_stride": stride},
     }
     if has_unmask:
-        un_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(un0, un1)]))
+        un_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(un0[:n_un], un1[:n_un])]))
         # eligible rows shrink by the commits of each step; average over the steps of a block
         elig0 = int(((d["mask"] == 1) & (d["scaffold_mask"] == 0)).sum())
         st_host = st["mask"].cpu().numpy()
         res["roofline_unmask"] = {
             "kernel": "vocab_reduce_kernel+block_select_kernel", "bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS,
-            "avg_call_us": round(un_ms * 1e3, 2), "eligible_rows_at_block_start": elig0,
+            "avg_call_us": round(un_ms * 1e3, 2), "calls_timed": n_un, "eligible_rows_at_block_start": elig0,
             "eligible_rows_now": int(((st_host == 1) & (d["scaffold_mask"] == 0)).sum()),
         }
         # forced single commit per block per step at these logit statistics: rows = elig0 - N * (step in block)
