@@ -35,7 +35,7 @@ namespace {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int RTHREADS = 256;
 #ifndef FDD_UNROLL
-#define FDD_UNROLL 4
+#define FDD_UNROLL 6
 #endif
 #ifndef FDD_PIECE_KB
 #define FDD_PIECE_KB 64
@@ -197,11 +197,20 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
                 absorb<VEC>(tr, x, (int)(body0 + (i + u * RTHREADS) * VEC));
             }
         }
-        for (; i < nvec; i += RTHREADS) {
-            const u32x4 raw = __builtin_nontemporal_load(vp + i);
-            float x[VEC];
-            widen(raw, x);
-            absorb<VEC>(tr, x, (int)(body0 + i * VEC));
+        if (i < nvec) {
+            // the ragged last group: its loads are requested together as well
+            u32x4 raw[UNROLL - 1];
+#pragma unroll
+            for (int u = 0; u < UNROLL - 1; ++u)
+                if (i + u * RTHREADS < nvec) raw[u] = __builtin_nontemporal_load(vp + i + u * RTHREADS);
+#pragma unroll
+            for (int u = 0; u < UNROLL - 1; ++u) {
+                if (i + u * RTHREADS < nvec) {
+                    float x[VEC];
+                    widen(raw[u], x);
+                    absorb<VEC>(tr, x, (int)(body0 + (i + u * RTHREADS) * VEC));
+                }
+            }
         }
         const long long ntail = v_hi - tail0;
         if (tid < ntail) {
