@@ -256,6 +256,58 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(CombineArgs a)
         n_seg = wg_of_unit((M + 1) * a.TPU - 1, a.base, a.rem) - wg_of_unit(M * a.TPU, a.base, a.rem) + 1;
     }
     if (n_seg == 1) return;     // written in final form by its only segment
+    if (a.SG == 1 && n_seg <= 4) {
+        // few segments: every thread reads the (m, l) pairs of its row itself, together with its
+        // partial outputs, in one round trip to memory and without LDS (same sums, same order)
+        const int rit = rit0 + r;
+        const int row = mt * a.mrows + rit;
+        if (rit >= a.mrows || row >= a.R) return;
+        const size_t prow = ((size_t)M * a.max_seg) * a.mrows + rit;
+        float2 ml[4];
+        float4 x[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            ml[u] = make_float2(-INFINITY, 0.f);
+            x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (u < n_seg) {
+                ml[u] = *reinterpret_cast<const float2*>(a.ws_ml + (prow + (size_t)u * a.mrows) * 2);
+                x[u] = *reinterpret_cast<const float4*>(a.ws_o + (prow + (size_t)u * a.mrows) * a.D + d4 * 4);
+            }
+        }
+        float mstar = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) mstar = fmaxf(mstar, ml[u].x);
+        float l = 0.f;
+        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u < n_seg) {
+                const float w = exp2f((ml[u].x - mstar) * a.c);
+                l = fmaf(ml[u].y, w, l);
+                acc.x = fmaf(x[u].x, w, acc.x);
+                acc.y = fmaf(x[u].y, w, acc.y);
+                acc.z = fmaf(x[u].z, w, acc.z);
+                acc.w = fmaf(x[u].w, w, acc.w);
+            }
+        }
+        const float inv = 1.f / l;
+        const int sel = row / a.G, g = row - sel * a.G;
+        const int nb = position_of(a.qpos, sel, a.NB);
+        const size_t off = (size_t)(pb * a.o_bs) + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * a.D + d4 * 4;
+        if (a.bf16) {
+            typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+            bf16x4 w4;
+            w4[0] = (__bf16)(acc.x * inv);
+            w4[1] = (__bf16)(acc.y * inv);
+            w4[2] = (__bf16)(acc.z * inv);
+            w4[3] = (__bf16)(acc.w * inv);
+            *reinterpret_cast<bf16x4*>(static_cast<uint16_t*>(a.out) + off) = w4;
+        } else {
+            *reinterpret_cast<float4*>(static_cast<float*>(a.out) + off) =
+                make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+        }
+        return;
+    }
     float* const sm = smem;                           // [RB][n_seg] segment maxima
     float* const sl = smem + a.RB * n_seg;            // [RB][n_seg] segment sums
     float4* const red = reinterpret_cast<float4*>(smem + ((2 * a.RB * a.max_seg + 3) & ~3));   // [RB][SG][d4n]
