@@ -84,6 +84,9 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
+#ifndef FDD_ODD_XCD_WEIGHT
+#define FDD_ODD_XCD_WEIGHT 97     // share of a piece on an odd XCD, in per cent of one on an even XCD
+#endif
 constexpr int KT = 64;           // keys per tile
 constexpr int NB = 4;            // ring slots per operand in LDS
 typedef short i16x4 __attribute__((ext_vector_type(4)));
@@ -116,7 +119,8 @@ struct Args {
     int ttpr;       // private tiles per rollout: extension tiles, then block tiles
     const int32_t* qpos;   // stacked rows are the listed block positions only (ascending n*B + b), or nullptr: all of them
     int NB;         // N * B
-    FastDiv dMT, dS, dTPU, dHkv, dG, dB, dBG, dTTPR, dBase, dBase1;   // divisions by launch constants
+    FastDiv dMT, dS, dTPU, dHkv, dG, dB, dBG, dTTPR, dBase, dBase1, dPerXcd;   // divisions by launch constants
+    int w_even, w_odd;   // equal pieces: weight of a piece by the parity of the XCD it runs on
 };
 
 template <int D, int WAVES>
@@ -200,8 +204,24 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         const int khv_ = fast_div(rest, a.dS);
         piece = rest - khv_ * a.S;
         M = khv_ * a.MT + mt_;
-        t_begin = fast_div(a.TPU * piece, a.dS);
-        todo = fast_div(a.TPU * (piece + 1), a.dS) - t_begin;
+        if (a.w_odd == a.w_even) {
+            t_begin = fast_div(a.TPU * piece, a.dS);
+            todo = fast_div(a.TPU * (piece + 1), a.dS) - t_begin;
+        } else {
+            // The share of a piece follows the speed of the XCD it runs on (measured: the odd XCD of a
+            // pair streams the same tiles a few per cent slower).  Every piece of the M-tile works out
+            // the same boundaries: unit TPU * (weights before it) / (all weights).
+            int cum = 0, lo = 0, hi = 0;
+            for (int p = 0; p < a.S; ++p) {
+                const int x = fast_div((khv_ * a.S + p) * a.MT + mt_, a.dPerXcd);
+                const int wgt = (x & 1) ? a.w_odd : a.w_even;
+                lo = p == piece ? cum : lo;
+                cum += wgt;
+                hi = p == piece ? cum : hi;
+            }
+            t_begin = (a.TPU * lo) / cum;
+            todo = (a.TPU * hi) / cum - t_begin;
+        }
     } else {
         const int u0 = unit_begin(wg, a.base, a.rem);
         todo = unit_begin(wg + 1, a.base, a.rem) - u0;
@@ -865,6 +885,10 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.dTTPR = make_fastdiv((uint32_t)a.ttpr);
     a.dBase = make_fastdiv((uint32_t)(a.base > 0 ? a.base : 1));
     a.dBase1 = make_fastdiv((uint32_t)(a.base + 1));
+    a.dPerXcd = make_fastdiv((uint32_t)a.per_xcd);
+    // (with 2..16 pieces of 32 units or more a shift of 3 % is at least one unit)
+    a.w_even = 100;
+    a.w_odd = (a.S >= 2 && a.S <= 16 && a.TPU >= 32 * a.S) ? FDD_ODD_XCD_WEIGHT : 100;
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;
     if (plan.packed)
         return p.D == 128 ? launch<128, 8, true>(a, pack_now, s, before_main) : launch<64, 8, true>(a, pack_now, s, before_main);
