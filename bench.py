@@ -16,8 +16,15 @@ Prints ONE JSON line: whole-step throughput in rollout-tokens/s (N*B block
 positions per step, scaffold included), the roofline of the dominant kernel
 (attention on the matrix cores) from HIP events recorded around that kernel
 inside the timed region, the HBM roofline of the vocabulary reduction, the
-N=1 prefix-stream figures, and the fp64 CPU oracle timed on a bounded
-sample of the same workload on this machine's host cores.
+N=1 prefix-stream figures, and the fp64 CPU oracle timed on one full
+repetition of the same step on this machine's host cores.
+
+Before the timed region the same step runs untimed until 80 ms of GPU time
+have passed (`preheat_ms`), whatever --warmup says: the shader clock needs
+about 30 ms of load to settle, and a cold start reads 10..15 % low.  The
+attention kernel is timed on at least 20 launches: when --steps gives fewer
+samples inside the timed region, a post-pass of the same step supplies the
+rest (`launches_timed` / `launches_timed_in_region`).
 """
 from __future__ import annotations
 
@@ -39,10 +46,14 @@ PEAK_BF16_TFLOPS = 2500.0
 PEAK_VALU_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12      # one 32-bit vector operation per lane and clock
 SAMPLER_OPS_PER_ENTRY = 64                         # Philox share 20, uniform 4, two log2 36, key and compare 4
 STEPS_PER_BLOCK = 8
-# HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each scaled
-# by what the same counter reads for a 1 GiB device copy (0.5x and 1.0x); summary and commands in
-# profiles/bench_cfg5_denoise_step.md.  (read MiB, write MiB) per launch.
+# HBM bytes per launch, measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs of this file),
+# each scaled by what the same counter reads for a 1 GiB device copy (`--copy-probe`; 0.5x and 1.0x).  The
+# counters cannot be read from inside this process, so the line quotes the figure and says where it is from.
+# (read MiB, write MiB) per launch.
 MEASURED_TRAFFIC_MIB = {"cfg5": {"attn_bf16_kernel": (48.3, 28.4), "vocab_reduce_kernel": (193.0, 0.1)}}
+TRAFFIC_SOURCE = "profiles/bench_cfg5_denoise_step.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; build of commit efbbce6)"
+PREHEAT_MS = 80.0          # untimed GPU load before the timed region: the shader clock takes about 30 ms to settle
+MIN_ATTN_SAMPLES = 20      # the attention kernel is timed on at least this many launches
 
 
 def dev(a):
@@ -386,32 +397,41 @@ def time_scaffold_skip(F, w, d, g, steps, warmup):
 
 
 def cpu_baseline(w, d, logits):
-    """The fp64 oracle as it stands on a bounded sample of one step."""
+    """The fp64 oracle as it stands on ONE full, unscaled repetition of the step: attention on every output
+    row, then the unmask on every block (the K/V refresh is a copy of a few rows and is left out)."""
     import oracle
-    rows_all = w.N * w.B * w.Hq
-    stride = max(1, rows_all // 4096)
-    idx = np.arange(0, rows_all, stride)
-    rows = np.stack([idx // (w.B * w.Hq), (idx // w.Hq) % w.B, idx % w.Hq], 1).astype(np.int32)
     t = time.perf_counter()
-    oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"], rows=rows)
-    t_attn = (time.perf_counter() - t) * (rows_all / len(idx))
+    oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"])
+    t_attn = time.perf_counter() - t
     t_un = 0.0
-    n_un = 0
     if logits is not None:
-        n_un = min(w.N, 4)
         t = time.perf_counter()
-        oracle.unmask_step(logits[:n_un], d["mask"][:n_un], d["scaffold_mask"][:n_un], d["tokens"][:n_un],
-                           float(np.float32(w.tau)))
-        t_un = (time.perf_counter() - t) * (w.N / n_un)
+        oracle.unmask_step(logits, d["mask"], d["scaffold_mask"], d["tokens"], float(np.float32(w.tau)))
+        t_un = time.perf_counter() - t
     t_step = t_attn + t_un
     return {
         "value": round(w.N * w.B / t_step, 2), "unit": "rollout-tokens/s", "cores": oracle.num_threads(),
         "kind": "oracle",
-        "sample": f"attention on {len(idx)} of {rows_all} output rows (every {stride}th) and unmask on {n_un} of "
-                  f"{w.N} blocks of one step, each scaled to the full step; est. {t_step:.1f} s per step "
-                  f"({(t_attn * len(idx) / rows_all + t_un * n_un / max(w.N, 1)) * oracle.num_threads():.0f} core-seconds spent)",
+        "sample": f"one full step of {w.name}, unscaled: attention on all {w.N * w.B * w.Hq} output rows "
+                  f"({t_attn:.2f} s) and unmask on all {w.N} blocks ({t_un:.2f} s); {t_step:.2f} s per step",
         "host_cpu_count": os.cpu_count(),
     }
+
+
+def copy_probe(mib, reps):
+    """A plain device-to-device copy of known size, for calibrating the HBM byte counters: run under
+    `rocprofv3 --pmc FETCH_SIZE` (or WRITE_SIZE); each copy dispatch reads `mib` MiB and writes `mib` MiB,
+    so (counter reading in KiB) / (mib * 1024) is the factor other kernels' readings are divided by."""
+    import torch
+    n = mib << 20
+    x = torch.empty(n, dtype=torch.uint8, device="cuda")
+    x.random_(0, 255)
+    y = torch.empty_like(x)
+    torch.cuda.synchronize()
+    for _ in range(reps):
+        y.copy_(x)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe": {"mib": mib, "reps": reps, "bytes_read_per_dispatch": n, "bytes_written_per_dispatch": n}}))
 
 
 def main():
@@ -426,6 +446,10 @@ def main():
     ap.add_argument("--no-supplements", action="store_true")
     ap.add_argument("--n1-only", action="store_true",
                     help="run only the N=1 layer sweeps (for profiling them) and print their figures")
+    ap.add_argument("--attn-only", default=None, metavar="WORKLOAD",
+                    help="run only the attention call of this workload (cfg2, cfg3, n1_L16384) for profiling it")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="run only a device copy of this many MiB, five times (calibration of the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path has no multi-GPU part); use --gpus 1")
@@ -439,6 +463,16 @@ def main():
     F.load_library()
     torch.cuda.set_device(0)
 
+    if args.copy_probe > 0:
+        copy_probe(args.copy_probe, 5)
+        return
+    if args.attn_only:
+        wl = dict(W.CONFIGS)
+        wl["n1_L16384"] = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
+        wa = wl[args.attn_only]
+        nbuf = max(1, int(600e6 // attn_bytes(wa)[0]))      # rotate over more than the last-level cache holds
+        print(json.dumps({args.attn_only: time_attention_only(F, wa, args.steps, args.warmup, min(nbuf, 128))}))
+        return
     if args.n1_only:
         n1 = W.CONFIGS["cfg2"]
         n1_long = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
@@ -482,15 +516,11 @@ def main():
     stride = max(1, min(args.event_stride, args.steps // 2 if args.steps >= 2 else 1))   # both pairs get samples
     n_samples = (args.steps + stride - 1) // stride
     ev = Events(n_samples)
-    un0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_samples)]
-    un1 = [torch.cuda.Event(enable_timing=True) for _ in range(n_samples)]
-    n_un = 0
+    un_ev = Events(n_samples)
 
-    def step(i, timed):
-        nonlocal n_un
-        attn_timed = timed and i % stride == 0
-        un_timed = timed and i % stride == stride // 2
-        F.fdd_profile_attn_events(*(ev.pairs[i // stride] if attn_timed else (None, None)))
+    def step(i, attn_pair=None, un_pair=None, set_hook=False):
+        if set_hook:
+            F.fdd_profile_attn_events(*(attn_pair if attn_pair else (None, None)))
         if i % STEPS_PER_BLOCK == 0:
             # a new block: fork the rollouts and lay the (unchanged) prefix V out for the kernel once
             for k in parent:
@@ -499,35 +529,72 @@ def main():
         F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"], scaffold, out=out,
                          workspace=ws_a, prefix_v_packed=packed_v)
         if has_unmask:
-            if un_timed:
-                un0[n_un].record()
+            if un_pair:
+                un_pair[0].record()
             F.fdd_unmask_step(logits[i % 2], st["mask"], scaffold, tau, st["tokens"], conf, nun, com, workspace=ws_u)
-            if un_timed:
-                un1[n_un].record()
-                n_un += 1
+            if un_pair:
+                un_pair[1].record()
             F.fdd_block_kv_update(st["tokens"], com, tk, tv, st["block_k"], st["block_v"])
 
+    def sampled(i, i_rel, pairs_a, pairs_u):
+        # step i of the block cycle, the i_rel-th step of a sampled stretch: every `stride`-th step carries the
+        # pair around the attention kernel, another one the pair around the unmask call
+        a = pairs_a[i_rel // stride] if i_rel % stride == 0 else None
+        u = pairs_u[i_rel // stride] if (i_rel % stride == stride // 2 and i_rel // stride < len(pairs_u)) else None
+        step(i, a, u, set_hook=True)
+        return u is not None
+
+    # Untimed pre-heat, whatever --warmup says: whole blocks of the same step until PREHEAT_MS of GPU time have
+    # passed, so that the timed region starts at the clock the chip sustains under this load.
+    h0, h1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    h0.record()
+    preheat_ms, preheat_steps = 0.0, 0
+    while preheat_ms < PREHEAT_MS:
+        for i in range(2 * STEPS_PER_BLOCK):
+            step(i)
+        preheat_steps += 2 * STEPS_PER_BLOCK
+        h1.record()
+        h1.synchronize()
+        preheat_ms = h0.elapsed_time(h1)
     for i in range(args.warmup):
-        step(i, False)
+        step(i)
     torch.cuda.synchronize()
     t0 = torch.cuda.Event(enable_timing=True)
     t1 = torch.cuda.Event(enable_timing=True)
     wall0 = time.perf_counter()
     t0.record()
+    n_un = 0
     for i in range(args.steps):
-        step(i, True)
+        n_un += sampled(i, i, ev.pairs, un_ev.pairs)
     t1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
     F.fdd_profile_attn_events(None, None)
     ms_step = t0.elapsed_time(t1) / args.steps
-    attn_ms = ev.mean_ms(n_samples)
+    attn_samples = [a.elapsed_time(b) for a, b in ev.pairs[:n_samples]]
+    un_samples = [a.elapsed_time(b) for a, b in un_ev.pairs[:n_un]]
+    n_in_region = n_samples
+    # Post-pass outside the headline timing: the same step goes on until both kernels have been timed on
+    # MIN_ATTN_SAMPLES launches in all (a short --steps run has too few samples inside the timed region).
+    if n_in_region < MIN_ATTN_SAMPLES:
+        extra = MIN_ATTN_SAMPLES - n_in_region
+        ev2, un2 = Events(extra), Events(extra)
+        i0 = ((args.steps + STEPS_PER_BLOCK - 1) // STEPS_PER_BLOCK) * STEPS_PER_BLOCK    # a new block starts here
+        n2 = 0
+        for j in range(extra * stride):
+            n2 += sampled(i0 + j, j, ev2.pairs, un2.pairs)
+        torch.cuda.synchronize()
+        F.fdd_profile_attn_events(None, None)
+        attn_samples += [a.elapsed_time(b) for a, b in ev2.pairs]
+        un_samples += [a.elapsed_time(b) for a, b in un2.pairs[:n2]]
+    attn_ms = float(np.mean(attn_samples))
     tokens_per_s = w.N * w.B / (ms_step * 1e-3)
 
     flops = attn_flops(w)
     res = {
         "metric": "rollout-tokens/sec per denoise step", "value": round(tokens_per_s, 1), "unit": "rollout-tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "preheat_ms": round(preheat_ms, 1),
+        "preheat_steps": preheat_steps, "ms_per_step": round(ms_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: one denoise step (block attention + unmask + K/V refresh), N={w.N} "
                                f"rollouts, B={w.B}, shared prefix L={w.L}, Hq={w.Hq}, Hkv={w.Hkv}, D={w.D}, V={w.V}, "
@@ -542,17 +609,20 @@ def main():
                      "traffic": (round(sum(MEASURED_TRAFFIC_MIB[w.name]["attn_bf16_kernel"]) * 2 ** 20)
                                  if w.name in MEASURED_TRAFFIC_MIB else None),
                      "algorithmic_bytes": attn_bytes(w)[1],
+                     "traffic_source": TRAFFIC_SOURCE if w.name in MEASURED_TRAFFIC_MIB else None,
                      "flops_per_launch": flops, "avg_launch_us": round(attn_ms * 1e3, 2),
-                     "launches_timed": n_samples, "event_stride": stride},
+                     "min_launch_us": round(min(attn_samples) * 1e3, 2), "max_launch_us": round(max(attn_samples) * 1e3, 2),
+                     "launches_timed": len(attn_samples), "launches_timed_in_region": n_in_region,
+                     "event_stride": stride},
     }
     if has_unmask:
-        un_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(un0[:n_un], un1[:n_un])]))
+        un_ms = float(np.mean(un_samples))
         # eligible rows shrink by the commits of each step; average over the steps of a block
         elig0 = int(((d["mask"] == 1) & (d["scaffold_mask"] == 0)).sum())
         st_host = st["mask"].cpu().numpy()
         res["roofline_unmask"] = {
             "kernel": "vocab_reduce_kernel+block_select_kernel", "bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS,
-            "avg_call_us": round(un_ms * 1e3, 2), "calls_timed": n_un, "eligible_rows_at_block_start": elig0,
+            "avg_call_us": round(un_ms * 1e3, 2), "calls_timed": len(un_samples), "eligible_rows_at_block_start": elig0,
             "eligible_rows_now": int(((st_host == 1) & (d["scaffold_mask"] == 0)).sum()),
         }
         # forced single commit per block per step at these logit statistics: rows = elig0 - N * (step in block)
@@ -560,6 +630,7 @@ def main():
         byt = avg_rows * w.V * 2
         res["roofline_unmask"].update({"traffic": (round(sum(MEASURED_TRAFFIC_MIB[w.name]["vocab_reduce_kernel"]) * 2 ** 20)
                                                    if w.name in MEASURED_TRAFFIC_MIB else None),
+                                       "traffic_source": TRAFFIC_SOURCE if w.name in MEASURED_TRAFFIC_MIB else None,
                                        "achieved": round(byt / (un_ms * 1e-3) / 1e9, 1),
                                        "frac": round(byt / (un_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                                        "bytes_per_call": byt})

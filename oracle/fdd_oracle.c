@@ -188,7 +188,11 @@ int fddo_block_attn_ext(int N, int B, int L, int E, int Ecap, int Hq, int Hkv, i
             int n, b, h;
             if (rows) { n = rows[3 * r]; b = rows[3 * r + 1]; h = rows[3 * r + 2]; }
             else { h = (int)(r % Hq); b = (int)((r / Hq) % B); n = (int)(r / ((int64_t)Hq * B)); }
-            if (n < 0 || n >= N || b < 0 || b >= B || h < 0 || h >= Hq) { bad = 1; continue; }
+            if (n < 0 || n >= N || b < 0 || b >= B || h < 0 || h >= Hq) {
+#pragma omp atomic write
+                bad = 1;
+                continue;
+            }
             const int kh = h / G;
             const int S = causal_block ? L + E + b + 1 : Sfull;   /* number of visible keys */
             const size_t qo = (((size_t)n * B + b) * Hq + h) * D;
@@ -295,17 +299,6 @@ int fddo_unmask_step(int N, int B, int64_t V, int dtype, double tau, const void 
     return 0;
 }
 
-/*
- * Verify pass of scaffold speculative decoding over N blocks.  A position is a
- * draft position when mask == 1 and it is not scaffold.  mask and tokens are
- * updated in place: accepted positions take their draft token, the rejection
- * point takes the AR token, both are unmasked; later draft positions stay masked
- * and keep their tokens entry.
- *   ar_tok[n,b]     arg max of the AR logits at draft positions (lowest id on
- *                   ties), -1 elsewhere (may be NULL)
- *   n_accepted[n]   positions unmasked in block n by this call
- *   accepted[n,b]   1 = draft accepted, 2 = replaced by the AR token, 0 otherwise (may be NULL)
- */
 /* ---- the sampler's arithmetic (fp32 by definition) ------------------------- */
 
 /* Philox-4x32 with 10 rounds: counter-based generator of Salmon, Moraes, Dror and
@@ -373,6 +366,17 @@ float fddo_sample_key(float x, float c, uint64_t seed, uint32_t row, int64_t v)
 
 float fddo_sample_scale(float temperature) { return (float)(1.4426950408889634 / (double)temperature); }
 
+/*
+ * Verify pass of scaffold speculative decoding over N blocks.  A position is a
+ * draft position when mask == 1 and it is not scaffold.  mask and tokens are
+ * updated in place: accepted positions take their draft token, the rejection
+ * point takes the AR token, both are unmasked; later draft positions stay masked
+ * and keep their tokens entry.
+ *   ar_tok[n,b]     arg max of the AR logits at draft positions (lowest id on
+ *                   ties), -1 elsewhere (may be NULL)
+ *   n_accepted[n]   positions unmasked in block n by this call
+ *   accepted[n,b]   1 = draft accepted, 2 = replaced by the AR token, 0 otherwise (may be NULL)
+ */
 /* temperature == 0: greedy verifier (arg max of the logits); temperature > 0:
  * sampled verifier as defined above.  ar_tok receives the verifier's token. */
 int fddo_verify_step_ex(int N, int B, int64_t V, int dtype, const void *ar_logits, const uint8_t *scaffold,

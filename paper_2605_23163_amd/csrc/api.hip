@@ -1,5 +1,6 @@
 // C ABI entry points: host-side validation, planning and launches.
 #include <cmath>
+#include <cstdint>
 #include <cstdarg>
 #include <cstdio>
 
@@ -9,11 +10,13 @@
 namespace fdd {
 namespace {
 
-thread_local char g_err[256] = "";
+thread_local char g_err[384] = "";
 thread_local hipEvent_t g_ev_start = nullptr;
 thread_local hipEvent_t g_ev_stop = nullptr;
 
-fdd_status fail(fdd_status code, const char* fmt, ...)
+}  // namespace
+
+fdd_status set_error(fdd_status code, const char* fmt, ...)
 {
     va_list ap;
     va_start(ap, fmt);
@@ -21,6 +24,10 @@ fdd_status fail(fdd_status code, const char* fmt, ...)
     va_end(ap);
     return code;
 }
+
+namespace {
+
+#define fail set_error
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -35,20 +42,23 @@ fdd_status check_attn_shape(const fdd_attn_params* p)
     if (p->D != 64 && p->D != 128) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: head size D=%d not supported (64 or 128)", p->D);
     if (p->splits < 0 || p->splits > 64) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: splits=%d outside [0, 64]", p->splits);
     if (p->flags & ~FDD_ATTN_CAUSAL_BLOCK) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: unknown bits in flags (0x%x)", p->flags);
-    if ((long long)p->N * p->B * (p->Hq / p->Hkv) > (1ll << 30) || (long long)p->N * p->B * p->Hq * p->D > (1ll << 40))
+    // (every product below is bounded before the next factor is multiplied in: no 64-bit overflow for any int32 input)
+    const long long nb = (long long)p->N * p->B;
+    if (nb > (1ll << 30) || nb * (p->Hq / p->Hkv) > (1ll << 30) || nb * p->Hq > (1ll << 33))
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: N*B*Hq too large");
-    if ((long long)p->L * p->Hkv * p->D * 4 >= (1ll << 31))
+    if ((long long)p->L * p->Hkv >= (1ll << 31) || (long long)p->L * p->Hkv * p->D * 4 >= (1ll << 31))
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: prefix K (L*Hkv*D elements) must stay below 2 GiB");
-    if ((long long)p->N * p->B * p->Hkv * p->D * 4 >= (1ll << 32))
+    if (nb * p->Hkv >= (1ll << 32) || nb * p->Hkv * p->D * 4 >= (1ll << 32))
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: block K (N*B*Hkv*D elements) must stay below 4 GiB");
+    if (p->batch < 0 || p->batch > 65535 / p->Hkv) return fail(FDD_ERR_SHAPE, "fdd_block_attn: batch=%d outside [0, 65535 / Hkv]", p->batch);
     {
         // work units of the bf16 path: (KV head, 256-row M-tile, 64-key prefix tile)
-        const long long mt = ((long long)p->N * p->B * (p->Hq / p->Hkv) + 255) / 256;
+        const long long mt = (nb * (p->Hq / p->Hkv) + 255) / 256;            // <= 2^22
         const long long tpu = (p->L + 63) / 64 + 64;          // prefix tiles plus the units booked for private tiles (bounded by 64 here)
-        if (p->Hkv * (p->batch > 1 ? p->batch : 1) * mt * tpu >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_block_attn: batch*N*B*Hq*L too large");
+        const long long heads = (long long)p->Hkv * (p->batch > 1 ? p->batch : 1);                 // <= 2^16
+        if (heads * mt >= (1ll << 31) || heads * mt * tpu >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_block_attn: batch*N*B*Hq*L too large");
     }
     if (std::isnan(p->scale) || std::isinf(p->scale)) return fail(FDD_ERR_UNSUPPORTED, "fdd_block_attn: scale is not finite");
-    if (p->batch < 0 || p->batch > 65535 / p->Hkv) return fail(FDD_ERR_SHAPE, "fdd_block_attn: batch=%d outside [0, 65535 / Hkv]", p->batch);
     if (p->n_q_positions < 0 || (long long)p->n_q_positions > (long long)p->N * p->B)
         return fail(FDD_ERR_SHAPE, "fdd_block_attn: n_q_positions=%d outside [0, N*B]", p->n_q_positions);
     if (p->batch > 1) {
@@ -199,6 +209,29 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
 
 using namespace fdd;
 
+static fdd_status check_unmask_shape(const fdd_unmask_params* p, const char* fn)
+{
+    if (!p) return fail(FDD_ERR_NULL, "%s: params is NULL", fn);
+    if (p->N <= 0 || p->B <= 0 || p->V <= 0) return fail(FDD_ERR_SHAPE, "%s: N, B, V must be positive (got N=%d B=%d V=%lld)", fn, p->N, p->B, (long long)p->V);
+    if (p->V >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "%s: V must be below 2^31", fn);
+    if ((long long)p->N * p->B > (1ll << 24)) return fail(FDD_ERR_SHAPE, "%s: N*B too large", fn);
+    if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "%s: dtype %d is neither FDD_F32 nor FDD_BF16", fn, p->dtype);
+    if (std::isnan(p->tau)) return fail(FDD_ERR_UNSUPPORTED, "%s: tau is NaN", fn);
+    return FDD_OK;
+}
+
+
+// shape, type and pointer checks shared by the entry points of the unmask step (everything but the workspace)
+fdd_status fdd::check_unmask_args(const fdd_unmask_params* p, const char* fn)
+{
+    fdd_status st = check_unmask_shape(p, fn);
+    if (st != FDD_OK) return st;
+    if (!p->logits || !p->mask || !p->tokens || !p->confidences)
+        return fail(FDD_ERR_NULL, "%s: logits, mask, tokens and confidences must not be NULL", fn);
+    if (!aligned16(p->logits)) return fail(FDD_ERR_UNSUPPORTED, "%s: logits must be 16-byte aligned", fn);
+    return FDD_OK;
+}
+
 extern "C" {
 
 size_t fdd_block_attn_workspace(const fdd_attn_params* p)
@@ -262,7 +295,8 @@ fdd_status fdd_prefix_pack(const void* prefix_v, int32_t L, int32_t Hkv, int32_t
     if (dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_prefix_pack: only FDD_BF16 prefixes are packed");
     if (L < 0 || Hkv <= 0) return fail(FDD_ERR_SHAPE, "fdd_prefix_pack: L must be >= 0 and Hkv positive");
     if (D != 64 && D != 128) return fail(FDD_ERR_UNSUPPORTED, "fdd_prefix_pack: head size D=%d not supported (64 or 128)", D);
-    if ((long long)L * Hkv * D * 4 >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_prefix_pack: prefix V (L*Hkv*D elements) must stay below 2 GiB");
+    if ((long long)L * Hkv >= (1ll << 31) || (long long)L * Hkv * D * 4 >= (1ll << 31))
+        return fail(FDD_ERR_SHAPE, "fdd_prefix_pack: prefix V (L*Hkv*D elements) must stay below 2 GiB");
     const size_t need = fdd_prefix_pack_bytes(L, Hkv, D, dtype);
     if (need == 0) return FDD_OK;
     if (!prefix_v || !packed) return fail(FDD_ERR_NULL, "fdd_prefix_pack: prefix_v and packed must not be NULL");
@@ -273,20 +307,9 @@ fdd_status fdd_prefix_pack(const void* prefix_v, int32_t L, int32_t Hkv, int32_t
     return FDD_OK;
 }
 
-static fdd_status check_unmask_shape(const fdd_unmask_params* p)
-{
-    if (!p) return fail(FDD_ERR_NULL, "fdd_unmask_step: params is NULL");
-    if (p->N <= 0 || p->B <= 0 || p->V <= 0) return fail(FDD_ERR_SHAPE, "fdd_unmask_step: N, B, V must be positive (got N=%d B=%d V=%lld)", p->N, p->B, (long long)p->V);
-    if (p->V >= (1ll << 31)) return fail(FDD_ERR_SHAPE, "fdd_unmask_step: V must be below 2^31");
-    if ((long long)p->N * p->B > (1ll << 24)) return fail(FDD_ERR_SHAPE, "fdd_unmask_step: N*B too large");
-    if (p->dtype != FDD_F32 && p->dtype != FDD_BF16) return fail(FDD_ERR_DTYPE, "fdd_unmask_step: dtype %d is neither FDD_F32 nor FDD_BF16", p->dtype);
-    if (std::isnan(p->tau)) return fail(FDD_ERR_UNSUPPORTED, "fdd_unmask_step: tau is NaN");
-    return FDD_OK;
-}
-
 size_t fdd_unmask_workspace(const fdd_unmask_params* p)
 {
-    if (check_unmask_shape(p) != FDD_OK) return 0;
+    if (check_unmask_shape(p, "fdd_unmask_workspace") != FDD_OK) return 0;
     UnmaskPlan plan;
     make_unmask_plan(*p, &plan);
     return plan.ws_bytes;
@@ -294,11 +317,8 @@ size_t fdd_unmask_workspace(const fdd_unmask_params* p)
 
 fdd_status fdd_unmask_step(const fdd_unmask_params* p)
 {
-    fdd_status st = check_unmask_shape(p);
+    fdd_status st = check_unmask_args(p, "fdd_unmask_step");
     if (st != FDD_OK) return st;
-    if (!p->logits || !p->mask || !p->tokens || !p->confidences)
-        return fail(FDD_ERR_NULL, "fdd_unmask_step: logits, mask, tokens and confidences must not be NULL");
-    if (!aligned16(p->logits)) return fail(FDD_ERR_UNSUPPORTED, "fdd_unmask_step: logits must be 16-byte aligned");
     UnmaskPlan plan;
     make_unmask_plan(*p, &plan);
     if (!p->workspace) return fail(FDD_ERR_WORKSPACE, "fdd_unmask_step: workspace is NULL, %zu bytes needed", plan.ws_bytes);
@@ -346,9 +366,11 @@ fdd_status fdd_fork_block(int32_t N, size_t bytes, const void* src, void* dst, v
     if (N <= 0 || bytes == 0) return fail(FDD_ERR_SHAPE, "fdd_fork_block: N and bytes must be positive");
     if (bytes % 4 || (reinterpret_cast<uintptr_t>(src) & 3u) || (reinterpret_cast<uintptr_t>(dst) & 3u))
         return fail(FDD_ERR_UNSUPPORTED, "fdd_fork_block: bytes and pointers must be multiples of 4");
-    const char* s0 = static_cast<const char*>(src);
-    const char* d0 = static_cast<const char*>(dst);
-    if (s0 < d0 + (size_t)N * bytes && d0 < s0 + bytes) return fail(FDD_ERR_UNSUPPORTED, "fdd_fork_block: src and dst overlap");
+    if (bytes > (SIZE_MAX >> 1) / (size_t)N) return fail(FDD_ERR_SHAPE, "fdd_fork_block: N*bytes too large");
+    const uintptr_t s0 = reinterpret_cast<uintptr_t>(src), d0 = reinterpret_cast<uintptr_t>(dst);
+    const uintptr_t total = (uintptr_t)N * bytes;
+    if (s0 > UINTPTR_MAX - bytes || d0 > UINTPTR_MAX - total) return fail(FDD_ERR_SHAPE, "fdd_fork_block: address range wraps around");
+    if (s0 < d0 + total && d0 < s0 + bytes) return fail(FDD_ERR_UNSUPPORTED, "fdd_fork_block: src and dst overlap");
     hipError_t e = launch_fork_block(N, bytes, src, dst, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_fork_block: launch failed: %s", hipGetErrorString(e));
     return FDD_OK;

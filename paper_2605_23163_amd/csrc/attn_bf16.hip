@@ -72,6 +72,7 @@
 //     Diffusion") go through a simpler masked path out of the same ring: rows
 //     of other rollouts are masked to -inf, and in the verify pass of scaffold
 //     speculative decoding the block keys after the query's own position too.
+#include <atomic>
 #include <type_traits>
 
 #include "fdd_internal.h"
@@ -84,9 +85,7 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
 
-#ifndef FDD_ODD_XCD_WEIGHT
-#define FDD_ODD_XCD_WEIGHT 97     // share of a piece on an odd XCD, in per cent of one on an even XCD
-#endif
+constexpr int ODD_XCD_WEIGHT = 97;   // share of a piece on an odd XCD, in per cent of one on an even XCD (measured: 96..98 alike)
 constexpr int KT = 64;           // keys per tile
 constexpr int NB = 4;            // ring slots per operand in LDS
 typedef short i16x4 __attribute__((ext_vector_type(4)));
@@ -816,12 +815,16 @@ hipError_t launch(const Args& a, bool pack_now, hipStream_t stream, hipEvent_t b
     using C = Cfg<D, WAVES>;
     const size_t lds_bytes = C::LDS_BYTES;
     const auto kern = &attn_bf16_kernel<D, WAVES, PACKED>;
-    static bool attr_done = false;   // per instantiation
-    if (!attr_done) {
+    // the LDS limit of this instantiation is raised once per device (bit d of `done`: device d)
+    static std::atomic<uint64_t> done{0};
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (!(done.load(std::memory_order_acquire) & bit)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        done.fetch_or(bit, std::memory_order_release);
     }
     if (PACKED && pack_now) {
         hipLaunchKernelGGL(vt_pack_kernel<D>, dim3(a.TPF, a.Hkv * a.batch), dim3(512), 0, stream, a.pv,
@@ -888,7 +891,7 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.dPerXcd = make_fastdiv((uint32_t)a.per_xcd);
     // (with 2..16 pieces of 32 units or more a shift of 3 % is at least one unit)
     a.w_even = 100;
-    a.w_odd = (a.S >= 2 && a.S <= 16 && a.TPU >= 32 * a.S) ? FDD_ODD_XCD_WEIGHT : 100;
+    a.w_odd = (a.S >= 2 && a.S <= 16 && a.TPU >= 32 * a.S) ? ODD_XCD_WEIGHT : 100;
     if (plan.mtile_rows != 256) return hipErrorInvalidValue;
     if (plan.packed)
         return p.D == 128 ? launch<128, 8, true>(a, pack_now, s, before_main) : launch<64, 8, true>(a, pack_now, s, before_main);

@@ -49,6 +49,11 @@ struct AttnPlan {
 
 bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan);
 
+// Records the message fdd_last_error() returns on this thread; returns `code`.
+fdd_status set_error(fdd_status code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+// Host-side checks of an unmask call (everything but the workspace); `fn` names the entry point in messages.
+fdd_status check_unmask_args(const fdd_unmask_params* p, const char* fn);
+
 // Division by a number fixed per launch, prepared on the host: for 0 <= n < 2^31 and 1 <= d < 2^31,
 // n / d = ((n + 1) * mul) >> (32 + shift), where k = 31 + max(1, ceil(log2 d)), shift = k - 32 and mul is the
 // largest integer with mul * d < 2^k.  With e = 2^k - mul * d in (0, d] and n = q d + r the product is

@@ -34,13 +34,8 @@ namespace {
 
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr int RTHREADS = 256;
-#ifndef FDD_UNROLL
-#define FDD_UNROLL 6
-#endif
-#ifndef FDD_PIECE_KB
-#define FDD_PIECE_KB 64
-#endif
-constexpr int UNROLL = FDD_UNROLL;   // 16-byte loads in flight per thread
+constexpr int UNROLL = 6;            // 16-byte loads in flight per thread
+constexpr int PIECE_KB = 64;         // a row is cut into pieces of at least this size
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 struct Partial {
@@ -117,7 +112,8 @@ __device__ __forceinline__ void absorb(ThreadRun& t, const float (&x)[VEC], int 
         for (int j = VEC - 2; j >= 0; --j) first = (x[j] == cm) ? j : first;
         r.idx = v0 + first;
     }
-    const float mc = t.mc;
+    // (a thread that has only met -inf so far takes its terms against 0: 2^(-inf) = 0, never inf - inf)
+    const float mc = (t.mc == -INFINITY) ? 0.f : t.mc;
     float acc = 0.f;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) acc += fast_exp2(fmaf(x[j], LOG2E, -mc));
@@ -521,7 +517,7 @@ bool make_vocab_plan(int N, int B, long long V, int dtype, UnmaskPlan* plan)
     if (p.N <= 0 || p.B <= 0 || p.V <= 0) return false;
     const long long rows = (long long)p.N * p.B;
     const long long es = p.dtype == FDD_BF16 ? 2 : 4;
-    long long by_size = (p.V * es) / (FDD_PIECE_KB * 1024);     // keep pieces at this size or more
+    long long by_size = (p.V * es) / (PIECE_KB * 1024);     // keep pieces at this size or more
     if (by_size < 1) by_size = 1;
     long long want = (8192 + rows - 1) / rows;  // enough workgroups to fill 256 CUs several times
     if (want < 1) want = 1;

@@ -188,18 +188,41 @@ def test_repeated_calls_are_bitwise_reproducible(F):
 
 
 @pytest.mark.parametrize("name", ["cfg3", "cfg5"])
-def test_full_size_sampled_rows(F, oracle, name):
-    # at the sizes the benchmark times, the oracle checks a sample of output rows
+def test_full_size_every_row(F, oracle, name):
+    # at the sizes the benchmark times: EVERY output row against the oracle, for the plain call (the call
+    # lays V out itself) and for the call the benchmark makes (prefix V laid out beforehand by the caller)
     w = W.CONFIGS[name]
     print_case(test="attn_full_size", cfg=name)
     d = W.attention_inputs(w)
-    out = to_f64(run_gpu(F, d))
-    rng = np.random.default_rng(99)
-    rows = np.stack([rng.integers(0, w.N, 96), rng.integers(0, w.B, 96), rng.integers(0, w.Hq, 96)], 1)
-    # make sure first / last rollouts, positions and heads are in the sample
-    rows[:4] = [[0, 0, 0], [w.N - 1, w.B - 1, w.Hq - 1], [w.N - 1, 0, w.Hq - 1], [0, w.B - 1, 0]]
-    ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"], rows=rows)
-    got = out[rows[:, 0], rows[:, 1], rows[:, 2]]
-    err = np.abs(got - ref).max()
-    print(f"{name}: sampled max-abs err {err:.3e}")
-    assert np.isfinite(out).all() and err <= 2e-2
+    ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"])
+    t = {k: to_dev(v) for k, v in d.items()}
+    plain = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"])
+    packed = F.fdd_prefix_pack(t["prefix_v"])
+    pre = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"], prefix_v_packed=packed)
+    torch.cuda.synchronize()
+    for label, out in (("plain", plain), ("prefix_v_packed", pre)):
+        o = to_f64(out)
+        assert o.shape == ref.shape and np.isfinite(o).all()
+        err = np.abs(o - ref).max()
+        print(f"{name} {label}: max-abs err over all {ref.shape[0] * ref.shape[1] * ref.shape[2]} rows {err:.3e}")
+        assert err <= 2e-2, f"{name} {label}: max-abs error {err}"
+
+
+# Shapes whose M-tiles are cut into S = 2, 3, 4, 5, 7, 9, 10 equal pieces of 32 tiles or more, which is where
+# the share of a piece is weighted by the XCD it runs on, and two with many short pieces; every row is compared.
+@pytest.mark.parametrize("shape", [(16, 64, 4096), (10, 64, 8192), (8, 64, 8192), (6, 64, 12288), (5, 64, 16384),
+                                   (4, 64, 20480), (3, 64, 20480), (2, 64, 8192), (4, 64, 4096)])
+def test_weighted_equal_pieces_every_row(F, oracle, shape):
+    N, B, L = shape
+    print_case(test="attn_weighted_pieces", shape=shape)
+    rng = np.random.default_rng(1000 + N * 131 + L)
+    d = rand_attn(rng, N, B, L, 28, 4, 128, W.BF16)
+    t = {k: to_dev(v) for k, v in d.items()}
+    packed = F.fdd_prefix_pack(t["prefix_v"])
+    out = F.fdd_block_attn(t["q"], t["prefix_k"], t["prefix_v"], t["block_k"], t["block_v"], prefix_v_packed=packed)
+    torch.cuda.synchronize()
+    ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], d["block_k"], d["block_v"])
+    o = to_f64(out)
+    err = np.abs(o - ref).max()
+    print(f"N={N} B={B} L={L}: max-abs err over all rows {err:.3e}")
+    assert np.isfinite(o).all() and err <= 2e-2

@@ -65,7 +65,6 @@ def test_config5_two_steps_in_the_bench_configuration(oracle):
     print_case(test="cfg5_bench_configuration")
     d = W.full_step_inputs(w, n_logit_steps=2)
     tau = float(np.float32(w.tau))
-    rng = np.random.default_rng(77)
     g = {k: to_dev(d[k]) for k in ("q", "prefix_k", "prefix_v", "table_k", "table_v")}
     scaffold = torch.from_numpy(d["scaffold_mask"]).cuda()
     o = {k: np.broadcast_to(d[k][:1], d[k].shape).copy() for k in ("block_k", "block_v", "tokens", "mask")}
@@ -89,22 +88,34 @@ def test_config5_two_steps_in_the_bench_configuration(oracle):
         F.fdd_unmask_step(tl, st["mask"], scaffold, tau, st["tokens"], conf, nun, com, workspace=ws_u)
         F.fdd_block_kv_update(st["tokens"], com, g["table_k"], g["table_v"], st["block_k"], st["block_v"])
         torch.cuda.synchronize()
-        pick = rng.choice(w.N * w.B * w.Hq, 256, replace=False)
-        rows = np.stack([pick // (w.B * w.Hq), (pick // w.Hq) % w.B, pick % w.Hq], 1).astype(np.int32)
-        ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], o["block_k"], o["block_v"], rows=rows)
-        err = np.abs(to_f64(out)[rows[:, 0], rows[:, 1], rows[:, 2]] - ref).max()
+        # every output row of the step against the oracle
+        ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], o["block_k"], o["block_v"])
+        err = np.abs(to_f64(out) - ref).max()
+        print(f"step {step}: attention max-abs err over all rows {err:.3e}", flush=True)
         assert err <= 2e-2, f"step {step}: attention max-abs {err}"
         r = oracle.unmask_step(logits, o["mask"], d["scaffold_mask"], o["tokens"], tau)
         elig = (o["mask"] == 1) & (d["scaffold_mask"] == 0)
         near = elig & (np.abs(r["confidences"] - tau) < 1e-3)
         assert not near.any()
-        # forced single commits compare confidences across positions: accept the oracle's runner-up when the two are within 1e-6
-        got_tok, got_mask = st["tokens"].cpu().numpy(), st["mask"].cpu().numpy()
+        # A forced single commit compares confidences across positions (fp32 sums on the GPU, fp64 in the
+        # oracle): when the two best fp64 confidences of a block are within 1e-6 relative, either position is a
+        # valid commit.  The oracle's state then follows the GPU's choice, so that the chain stays comparable.
+        got_tok, got_mask, got_com = st["tokens"].cpu().numpy(), st["mask"].cpu().numpy(), com.cpu().numpy()
         for n in range(w.N):
-            if not (np.array_equal(got_tok[n], r["tokens"][n]) and np.array_equal(got_mask[n], r["mask"][n])):
-                c = np.sort(r["confidences"][n][elig[n]])[::-1]
-                assert len(c) > 1 and (c[0] - c[1]) <= 1e-6 * c[0], f"step {step}, block {n}: decisions differ"
-                pytest.skip("forced-choice near-tie in the seeded data; pick another seed")
+            if np.array_equal(got_tok[n], r["tokens"][n]) and np.array_equal(got_mask[n], r["mask"][n]):
+                continue
+            c = np.sort(r["confidences"][n][elig[n]])[::-1]
+            forced = not (r["confidences"][n][elig[n]] >= tau).any()
+            assert forced and len(c) > 1 and (c[0] - c[1]) <= 1e-6 * c[0], f"step {step}, block {n}: decisions differ"
+            b = np.flatnonzero(got_com[n])
+            assert len(b) == 1 and elig[n, b[0]] and r["confidences"][n, b[0]] >= c[0] * (1 - 1e-6)
+            assert got_tok[n, b[0]] == r["candidates"][n, b[0]]
+            untouched = np.ones(w.B, dtype=bool)
+            untouched[b[0]] = False
+            np.testing.assert_array_equal(got_tok[n][untouched], o["tokens"][n][untouched])
+            np.testing.assert_array_equal(got_mask[n][untouched], o["mask"][n][untouched])
+            print(f"step {step}, block {n}: forced-commit near-tie, the GPU's candidate accepted", flush=True)
+            r["tokens"][n], r["mask"][n], r["committed"][n] = got_tok[n], got_mask[n], got_com[n]
         np.testing.assert_array_equal(nun.cpu().numpy(), r["n_unmasked"])
         np.testing.assert_allclose(conf.cpu().numpy()[elig], r["confidences"][elig], rtol=2e-5)
         o["tokens"], o["mask"] = r["tokens"], r["mask"]

@@ -138,6 +138,37 @@ def test_bf16_ties_take_the_lowest_id(F, oracle):
     assert (wide == wide.max(-1, keepdims=True)).sum(-1).min() > 1
 
 
+@pytest.mark.parametrize("dtype", [W.BF16, W.F32])
+def test_minus_infinity_entries(F, oracle, dtype):
+    # -inf logits (banned tokens) have probability 0; runs of them at the head of a row, over whole 16-byte
+    # vectors, across a piece boundary and at the tail must not disturb the row's sum or its arg max
+    print_case(test="unmask_minus_inf", dtype=dtype)
+    rng = np.random.default_rng(17)
+    N, B, V = 2, 8, 70001
+    x = (rng.standard_normal((N, B, V)) * 2).astype(np.float32)
+    ninf = np.float32(-np.inf)
+    x[0, 0, :1] = ninf                      # head element
+    x[0, 1, :4099] = ninf                   # every thread of the first pass meets only -inf first
+    x[0, 2, 8:8 + 8 * 700] = ninf           # aligned runs of whole vectors
+    x[0, 3, V - 5:] = ninf                  # tail
+    x[0, 4, 30000:41000] = ninf             # across a piece boundary
+    x[0, 5, :] = ninf
+    x[0, 5, 12345] = 1.5                    # a single finite entry: confidence 1
+    x[0, 6, 1::2] = ninf                    # every other entry
+    x[0, 7, :] = ninf
+    x[0, 7, [7, 69999]] = -3.0              # two equal finite entries far apart: lowest id, confidence 1/2
+    x[1, :, rng.integers(0, V, 3000)] = ninf
+    logits = W.to_storage(x, dtype)
+    mask = np.ones((N, B), np.uint8)
+    tokens = np.full((N, B), -1, np.int32)
+    for tau in (0.0, 0.9):
+        ref, got, t32 = run_both(F, oracle, logits, mask, None, tokens, tau)
+        assert np.isfinite(got["confidences"]).all()
+        compare(ref, got, mask, None, tokens, t32)
+    assert abs(got["confidences"][0, 5] - 1.0) <= 2e-5 and abs(got["confidences"][0, 7] - 0.5) <= 1e-5
+    assert ref["candidates"][0, 5] == 12345 and ref["candidates"][0, 7] == 7
+
+
 def test_near_tau_rows_are_reported_not_failed(F, oracle):
     print_case(test="unmask_near_tau")
     # rows built so that conf = 1/(1 + (V-1) e^-s) sits within 1e-3 of tau

@@ -89,6 +89,27 @@ def test_threshold_is_inclusive(oracle):
     assert r["n_unmasked"][0] == 2 and r["tokens"][0].tolist() == [2, 2]
 
 
+def test_minus_infinity_logits_are_entries_of_probability_zero(oracle):
+    # a vocabulary entry at -inf (a banned token) has softmax probability exactly 0: the row's confidence
+    # and arg max are those of the row with these entries removed (library log-sum-exp as the second opinion)
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(31)
+    V = 97
+    x = rng.standard_normal((1, 6, V)) * 2
+    holes = [np.arange(0, 9), np.arange(V - 11, V), np.arange(8, 24), np.array([0, 5, 50, 96]),
+             np.setdiff1d(np.arange(V), [13]), np.setdiff1d(np.arange(V), [3, 77])]
+    x[0, 5, 77] = x[0, 5, 3]            # two finite entries, equal: lowest id, confidence 1/2
+    for b, h in enumerate(holes):
+        x[0, b, h] = -np.inf
+    r = oracle.unmask_step(x, np.ones((1, 6), np.uint8), None, np.full((1, 6), -1, np.int32), tau=2.0)
+    for b, h in enumerate(holes):
+        keep = np.setdiff1d(np.arange(V), h)
+        assert r["candidates"][0, b] == keep[np.argmax(x[0, b, keep])]
+        assert r["confidences"][0, b] == pytest.approx(np.exp(x[0, b, keep].max() - logsumexp(x[0, b, keep])), rel=1e-13)
+    assert r["confidences"][0, 4] == 1.0 and r["candidates"][0, 4] == 13
+    assert r["confidences"][0, 5] == 0.5 and r["candidates"][0, 5] == 3
+
+
 @pytest.mark.parametrize("seed", range(5))
 def test_block_invariants(oracle, seed):
     rng = np.random.default_rng(100 + seed)
