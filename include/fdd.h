@@ -198,6 +198,26 @@ typedef struct fdd_unmask_params {
 size_t fdd_unmask_workspace(const fdd_unmask_params *p);
 fdd_status fdd_unmask_step(const fdd_unmask_params *p);
 
+/* fdd_unmask_step_static: fdd_unmask_step for callers that cannot allocate
+ * device memory and carry no workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * results bit for bit; `workspace` and `workspace_bytes` are ignored.  The
+ * per-piece partial results of the vocabulary reduction go to a fixed array of
+ * FDD_STATIC_SCRATCH_BYTES inside the library's device image instead (every GPU
+ * the library runs on holds one copy until the process ends).  The call
+ * allocates nothing and frees nothing.  Shapes whose partials do not fit
+ * (N*B*pieces > FDD_STATIC_SCRATCH_BYTES / 16, i.e. fdd_unmask_workspace() above
+ * that size; 1024 positions over V = 152064 need 64 KiB) are rejected with
+ * FDD_ERR_WORKSPACE and nothing is launched.  All calls on one GPU share that
+ * GPU's array: two calls that overlap in time on one GPU (different streams,
+ * different threads) race and give wrong results; calls ordered on one stream
+ * are safe.  Nothing in the array has to be cleared between calls: every
+ * record a call reads was written by that call.  The current device must be
+ * the one `stream` belongs to.
+ */
+#define FDD_STATIC_SCRATCH_BYTES ((size_t)1 << 20)
+fdd_status fdd_unmask_step_static(const fdd_unmask_params *p);
+
 /* ------------------------------------------------------------------------
  * fdd_verify_step: accept scan of Scaffold Speculative Decoding over N blocks
  * (paper, "Scaffold Speculative Decoding (SS)", steps 1 and 3).

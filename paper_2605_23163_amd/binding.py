@@ -16,7 +16,7 @@ _lib = None
 FDD_F32, FDD_BF16 = 0, 1
 FDD_ATTN_CAUSAL_BLOCK = 1
 EXPORTS = ("fdd_block_attn_workspace", "fdd_block_attn", "fdd_prefix_pack_bytes", "fdd_prefix_pack",
-           "fdd_unmask_workspace", "fdd_unmask_step", "fdd_verify_workspace", "fdd_verify_step",
+           "fdd_unmask_workspace", "fdd_unmask_step", "fdd_unmask_step_static", "fdd_verify_workspace", "fdd_verify_step",
            "fdd_fork_block", "fdd_block_kv_update", "fdd_block_commit", "fdd_traj_mean", "fdd_profile_attn_events", "fdd_last_error", "fdd_version")
 
 
@@ -97,6 +97,8 @@ def load_library():
         lib.fdd_unmask_workspace.argtypes = [C.POINTER(UnmaskParams)]
         lib.fdd_unmask_step.restype = C.c_int
         lib.fdd_unmask_step.argtypes = [C.POINTER(UnmaskParams)]
+        lib.fdd_unmask_step_static.restype = C.c_int
+        lib.fdd_unmask_step_static.argtypes = [C.POINTER(UnmaskParams)]
         lib.fdd_verify_workspace.restype = C.c_size_t
         lib.fdd_verify_workspace.argtypes = [C.POINTER(VerifyParams)]
         lib.fdd_verify_step.restype = C.c_int
@@ -360,6 +362,20 @@ def fdd_unmask_step(logits, mask, scaffold_mask, tau, tokens, confidences=None, 
     p.workspace_bytes = nbytes
     p.stream = _stream_ptr(stream)
     _check(lib.fdd_unmask_step(C.byref(p)))
+    return tokens, confidences, n_unmasked, committed
+
+
+def fdd_unmask_step_static(logits, mask, scaffold_mask, tau, tokens, confidences, n_unmasked, committed, stream=None):
+    """``fdd_unmask_step`` without a workspace and without any allocation: every
+    output tensor is the caller's, the partial results live in the library's
+    built-in device array.  Raises FddError when the shape needs more than that
+    array holds."""
+    lib = load_library()
+    p = _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed)
+    p.workspace = None
+    p.workspace_bytes = 0
+    p.stream = _stream_ptr(stream)
+    _check(lib.fdd_unmask_step_static(C.byref(p)))
     return tokens, confidences, n_unmasked, committed
 
 
