@@ -189,7 +189,7 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
     }
     if (partials) {
         const size_t prow = (size_t)NM * pl.max_seg * pl.mtile_rows;
-        pl.ws_o_bytes = (prow * p.D * sizeof(float) + 255) & ~(size_t)255;
+        pl.ws_o_bytes = (prow * p.D * (p.dtype == FDD_BF16 ? 2 : sizeof(float)) + 255) & ~(size_t)255;
         pl.ws_ml_bytes = (prow * 2 * sizeof(float) + 255) & ~(size_t)255;
     } else {
         pl.ws_o_bytes = 0;
@@ -277,7 +277,7 @@ fdd_status fdd_block_attn(const fdd_attn_params* p)
     if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: launch failed: %s", hipGetErrorString(e));
     if (timed && hipEventRecord(g_ev_stop, s) != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: cannot record the stop event");
     if (plan.ws_o_bytes > 0) {
-        e = launch_attn_combine(*p, plan, scale, s);
+        e = p->dtype == FDD_BF16 ? launch_attn_merge_bf16(*p, plan, scale, s) : launch_attn_combine(*p, plan, scale, s);
         if (e != hipSuccess) return fail(FDD_ERR_LAUNCH, "fdd_block_attn: merge launch failed: %s", hipGetErrorString(e));
     }
     return FDD_OK;

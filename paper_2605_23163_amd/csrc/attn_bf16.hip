@@ -97,8 +97,8 @@ struct Args {
     const uint16_t* bk;
     const uint16_t* bv;
     uint16_t* out;
-    float* ws_o;
-    float* ws_ml;
+    void* ws_o;      // partial averages, bf16, in accumulator order (see the epilogue)
+    float* ws_ml;    // partial (m, l) per row
     const uint16_t* vt;   // packed V^T tiles of the full prefix tiles (PACKED kernels only)
     const uint16_t* ek;   // per-rollout extension [N, Ecap, Hkv, D]
     const uint16_t* ev;
@@ -737,17 +737,24 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                         *reinterpret_cast<bf16x4*>(op + d) = w;
                     }
             } else {
-                const size_t prow = ((size_t)M * a.max_seg + seg) * MROWS + (wave * 32 + l32);
-                float* wo = a.ws_o + prow * D;
+                // Partial of this segment: the segment's own softmax average (o / l, rounded to bf16) and its
+                // (m, l) in fp32.  The averages lie in the order of the accumulator registers,
+                // [M-tile][segment][wavefront][register pair][lane] x 8 bf16, so every store instruction of a
+                // wavefront writes 1 KB in one piece and the merge kernel reads them the same way.
+                const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+                const size_t pseg = (size_t)M * a.max_seg + seg;
+                u32x4* wo = reinterpret_cast<u32x4*>(a.ws_o) + (pseg * WAVES + wave) * (size_t)(2 * DB * 64) + lane;
 #pragma unroll
                 for (int db = 0; db < DB; ++db)
 #pragma unroll
-                    for (int v4 = 0; v4 < 4; ++v4) {
-                        const int d = db * 32 + v4 * 8 + half * 4;
-                        float4 w = make_float4(o[db][v4 * 4 + 0], o[db][v4 * 4 + 1], o[db][v4 * 4 + 2], o[db][v4 * 4 + 3]);
-                        *reinterpret_cast<float4*>(wo + d) = w;
+                    for (int v2 = 0; v2 < 2; ++v2) {
+                        bf16x8 w;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) w[j] = (__bf16)(o[db][v2 * 8 + j] * inv);
+                        wo[(db * 2 + v2) * 64] = __builtin_bit_cast(u32x4, w);
                     }
                 if (half == 0) {
+                    const size_t prow = pseg * MROWS + (wave * 32 + l32);
                     a.ws_ml[prow * 2 + 0] = m_run;
                     a.ws_ml[prow * 2 + 1] = l_tot;
                 }
@@ -809,6 +816,142 @@ __global__ __launch_bounds__(512) void vt_pack_kernel(const uint16_t* __restrict
     }
 }
 
+// ---------------------------------------------------------------------------
+// Merge of the segments of an M-tile (log-sum-exp merge, paper-independent arithmetic of the split):
+//   m* = max_s m_s,   W_s = l_s 2^((m_s - m*) c) / sum_t l_t 2^((m_t - m*) c),   out = sum_s W_s avg_s
+// with avg_s the segment's own softmax average as the attention kernel left it (bf16, accumulator order).
+// The sum over s runs in a fixed order, so results are reproducible.
+// grid (M-tiles, 16 SG): a block of 256 threads = SG segment groups x 256/SG chunks of 8 channels of one
+// wavefront's 32 rows; thread (sg, chunk) sums segments sg, sg + SG, .., four loads in flight, and the SG partial
+// sums are added in the order sg = 0, 1, .. through LDS.  SG grows when rows are few and segments many (N = 1).
+struct MergeArgs {
+    const u32x4* ws_o;
+    const float* ws_ml;
+    uint16_t* out;
+    const int32_t* qpos;
+    long long o_bs;
+    int Hq, Hkv, G, R, MT, NB;
+    int max_seg, fixed_seg, TPU, base, rem;
+    int SG;
+    float c;
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_merge_bf16_kernel(MergeArgs a)
+{
+    constexpr int DB = D / 32;
+    constexpr int CPW = 2 * DB * 64;          // 16-byte chunks per wavefront of the attention kernel
+    constexpr int CH = 8 * CPW;               // chunks per M-tile and segment
+    extern __shared__ __align__(16) float smem[];
+    const int tid = (int)threadIdx.x;
+    const int M = (int)blockIdx.x;
+    int n_seg = a.fixed_seg;
+    if (n_seg == 0)     // same arithmetic as the attention kernel: workgroups whose unit range meets this M-tile
+        n_seg = wg_of_unit((M + 1) * a.TPU - 1, a.base, a.rem) - wg_of_unit(M * a.TPU, a.base, a.rem) + 1;
+    if (n_seg == 1) return;     // written in final form by its only segment
+    const int khv = M / a.MT, mt = M - khv * a.MT;      // (problem of the batch, KV head), M-tile
+    const int pb = khv / a.Hkv, kh = khv - pb * a.Hkv;
+    const int CPB = 256 / a.SG;               // chunks per block: 32 .. 256, all of one wavefront (32 rows)
+    const int c0 = (int)blockIdx.y * CPB;
+    const int wave = c0 / CPW;
+    const int row0 = mt * 256 + wave * 32;    // first stacked row of the block's 32 rows
+    if (row0 >= a.R) return;
+
+    // ---- weights of the segments, per row: 8 threads per row ----------------------------------
+    float* const W = smem;                            // [32][n_seg]
+    {
+        const int r = tid >> 3, j = tid & 7;
+        const bool live = row0 + r < a.R;
+        const float* ml = a.ws_ml + (((size_t)M * a.max_seg) * 256 + wave * 32 + r) * 2;
+        float mx = -INFINITY;
+        for (int s = j; s < n_seg; s += 8) {
+            float2 x = make_float2(-INFINITY, 0.f);
+            if (live) x = *reinterpret_cast<const float2*>(ml + (size_t)s * 512);
+            if (!(x.y > 0.f)) x.x = -INFINITY;        // a segment that saw no key of this row
+            W[r * n_seg + s] = x.x;
+            smem[32 * n_seg + r * n_seg + s] = x.y;
+            mx = fmaxf(mx, x.x);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 4, 64));
+        const float mref = mx == -INFINITY ? 0.f : mx;
+        float sum = 0.f;
+        for (int s = j; s < n_seg; s += 8) {
+            const float w = smem[32 * n_seg + r * n_seg + s] * exp2f((W[r * n_seg + s] - mref) * a.c);
+            W[r * n_seg + s] = w;
+            sum += w;
+        }
+        sum += __shfl_xor(sum, 1, 64);
+        sum += __shfl_xor(sum, 2, 64);
+        sum += __shfl_xor(sum, 4, 64);
+        const float inv = sum > 0.f ? 1.f / sum : 0.f;
+        for (int s = j; s < n_seg; s += 8) W[r * n_seg + s] *= inv;
+    }
+    __syncthreads();
+
+    // ---- weighted sum of the segments' averages -------------------------------------------------
+    const int sg = tid / CPB, cl = tid - sg * CPB;
+    const int cidx = c0 + cl;                          // chunk inside the M-tile: [wave][register pair][lane]
+    const int lane = cidx & 63, i2 = (cidx >> 6) % (2 * DB);
+    const int r = lane & 31, half = lane >> 5;
+    const bool live = row0 + r < a.R;
+    float acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = 0.f;
+    if (live) {
+        const u32x4* src = a.ws_o + ((size_t)M * a.max_seg) * CH + cidx;
+        for (int s0 = sg; s0 < n_seg; s0 += 4 * a.SG) {
+            u32x4 x[4];
+            float w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + u * a.SG;
+                w[u] = 0.f;
+                x[u] = u32x4{0u, 0u, 0u, 0u};
+                if (s < n_seg) {
+                    x[u] = src[(size_t)s * CH];
+                    w[u] = W[r * n_seg + s];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    // (a weight of 0 belongs to a segment without a key of this row: its average is 0 as well)
+                    acc[2 * j] = fmaf(__uint_as_float(x[u][j] << 16), w[u], acc[2 * j]);
+                    acc[2 * j + 1] = fmaf(__uint_as_float(x[u][j] & 0xffff0000u), w[u], acc[2 * j + 1]);
+                }
+        }
+    }
+    if (a.SG > 1) {
+        float* const red = smem + 2 * 32 * n_seg;     // [SG][CPB][8]
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; ++j) red[(sg * CPB + cl) * 8 + j] = acc[j];
+        __syncthreads();
+        if (sg != 0) return;
+        for (int k = 1; k < a.SG; ++k)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] += red[(k * CPB + cl) * 8 + j];
+    }
+    if (!live) return;
+    const int row = row0 + r;
+    const int sel = row / a.G, g = row - sel * a.G;
+    const int nb = a.qpos ? min(max(a.qpos[sel], 0), a.NB - 1) : sel;
+    const int db = i2 >> 1, v2 = i2 & 1;
+    uint16_t* op = a.out + pb * a.o_bs + ((size_t)nb * a.Hq + (size_t)kh * a.G + g) * D + db * 32 + v2 * 16 + half * 4;
+    typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+    bf16x4 lo, hi;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        lo[j] = (__bf16)acc[j];
+        hi[j] = (__bf16)acc[4 + j];
+    }
+    *reinterpret_cast<bf16x4*>(op) = lo;
+    *reinterpret_cast<bf16x4*>(op + 8) = hi;
+}
+
 template <int D, int WAVES, bool PACKED>
 hipError_t launch(const Args& a, bool pack_now, hipStream_t stream, hipEvent_t before_main)
 {
@@ -855,7 +998,7 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     a.bv = static_cast<const uint16_t*>(p.block_v);
     a.out = static_cast<uint16_t*>(p.out);
     char* ws = static_cast<char*>(p.workspace);
-    a.ws_o = reinterpret_cast<float*>(ws);
+    a.ws_o = ws;
     a.ws_ml = reinterpret_cast<float*>(ws + plan.ws_o_bytes);
     const bool pack_now = plan.packed && !p.prefix_v_packed;
     a.vt = pack_now ? reinterpret_cast<const uint16_t*>(ws + plan.ws_o_bytes + plan.ws_ml_bytes)
@@ -896,6 +1039,34 @@ hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, floa
     if (plan.packed)
         return p.D == 128 ? launch<128, 8, true>(a, pack_now, s, before_main) : launch<64, 8, true>(a, pack_now, s, before_main);
     return p.D == 128 ? launch<128, 8, false>(a, false, s, before_main) : launch<64, 8, false>(a, false, s, before_main);
+}
+
+hipError_t launch_attn_merge_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s)
+{
+    MergeArgs a;
+    a.ws_o = static_cast<const u32x4*>(p.workspace);
+    a.ws_ml = reinterpret_cast<const float*>(static_cast<const char*>(p.workspace) + plan.ws_o_bytes);
+    a.out = static_cast<uint16_t*>(p.out);
+    a.qpos = p.n_q_positions > 0 ? p.q_positions : nullptr;
+    a.o_bs = p.out_batch_stride;
+    const int batch = p.batch > 1 ? p.batch : 1;
+    a.Hq = p.Hq; a.Hkv = p.Hkv; a.G = plan.G; a.R = plan.R; a.MT = plan.MT; a.NB = p.N * p.B;
+    a.max_seg = plan.max_seg; a.fixed_seg = plan.uniform; a.TPU = plan.TPU;
+    a.base = (int)(plan.U / plan.W); a.rem = (int)(plan.U % plan.W);
+    a.c = scale * 1.4426950408889634f;
+    // more threads per chunk when the rows are few and the segments many
+    const long long rows = (long long)p.Hkv * batch * plan.R;
+    const int seg_hint = plan.uniform > 0 ? plan.uniform : plan.max_seg;
+    int sg = 1;
+    while (sg < 8 && sg * 2 <= seg_hint && rows * sg < 16384) sg *= 2;
+    a.SG = sg;
+    const int chunks = 8 * 2 * (p.D / 32) * 64;
+    const size_t smem = ((size_t)2 * 32 * plan.max_seg + (sg > 1 ? (size_t)256 * 8 : 0)) * sizeof(float);
+    if (smem > 60 * 1024 || plan.mtile_rows != 256) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(p.Hkv * batch * plan.MT), (unsigned)(chunks / (256 / sg)));
+    if (p.D == 128) hipLaunchKernelGGL(attn_merge_bf16_kernel<128>, grid, dim3(256), smem, s, a);
+    else hipLaunchKernelGGL(attn_merge_bf16_kernel<64>, grid, dim3(256), smem, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_prefix_pack(const void* prefix_v, int L, int Hkv, int D, void* packed, hipStream_t s)

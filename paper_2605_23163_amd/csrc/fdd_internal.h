@@ -41,7 +41,7 @@ struct AttnPlan {
     int uniform;      // bf16 path: > 0 when W = Hkv*MT*uniform, i.e. equal pieces per M-tile
     long long U;      // bf16 path: units in total
     int max_seg;      // partial slots per M-tile
-    size_t ws_o_bytes;   // partial outputs  [Hkv*MT][max_seg][mtile_rows][D] fp32
+    size_t ws_o_bytes;   // partial outputs  [Hkv*MT][max_seg][mtile_rows][D], fp32 (fp32 path) or bf16 (bf16 path)
     size_t ws_ml_bytes;  // partial (m, l)   [Hkv*MT][max_seg][mtile_rows][2] fp32
     size_t ws_vt_bytes;  // bf16 path: V of the full prefix tiles repacked for the P V fragments, or 0
     bool packed;         // bf16 path: the kernel reads repacked V (from the workspace or from the caller)
@@ -90,7 +90,8 @@ __host__ __device__ inline int wg_of_unit(int u, int base, int rem)
 hipError_t launch_attn_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s, hipEvent_t before_main);
 hipError_t launch_prefix_pack(const void* prefix_v, int L, int Hkv, int D, void* packed, hipStream_t s);
 hipError_t launch_attn_f32(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);
-hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);
+hipError_t launch_attn_combine(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);      // fp32 path
+hipError_t launch_attn_merge_bf16(const fdd_attn_params& p, const AttnPlan& plan, float scale, hipStream_t s);   // bf16 path
 
 // Vocabulary reduction: each eligible logits row is cut into `vsplits`
 // pieces; a piece leaves (max, argmax, sum exp(x - max)) in the workspace.

@@ -93,7 +93,8 @@ __device__ __forceinline__ void merge(Run& a, const Run& b)
     if (take_b) a.idx = b.idx;
 }
 
-template <int VEC>
+// SUM = false: only (max, arg max) are kept (the greedy verifier needs no probabilities)
+template <int VEC, bool SUM>
 __device__ __forceinline__ void absorb(ThreadRun& t, const float (&x)[VEC], int v0)
 {
     Run& r = t.r;
@@ -103,15 +104,18 @@ __device__ __forceinline__ void absorb(ThreadRun& t, const float (&x)[VEC], int 
     if (cm > r.m) {
         // this thread walks the row in ascending order, so a strictly larger
         // value is the only way its arg max can move
-        const float mc_new = cm * LOG2E;
-        r.s *= fast_exp2(t.mc - mc_new);      // (-inf - finite at the start: the sum is still 0)
+        if (SUM) {
+            const float mc_new = cm * LOG2E;
+            r.s *= fast_exp2(t.mc - mc_new);      // (-inf - finite at the start: the sum is still 0)
+            t.mc = mc_new;
+        }
         r.m = cm;
-        t.mc = mc_new;
         int first = VEC - 1;
 #pragma unroll
         for (int j = VEC - 2; j >= 0; --j) first = (x[j] == cm) ? j : first;
         r.idx = v0 + first;
     }
+    if (!SUM) return;
     // (a thread that has only met -inf so far takes its terms against 0: 2^(-inf) = 0, never inf - inf)
     const float mc = (t.mc == -INFINITY) ? 0.f : t.mc;
     float acc = 0.f;
@@ -130,8 +134,8 @@ __device__ __forceinline__ Run settle(const ThreadRun& t)
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
-// T = uint16_t (bf16 bits) or float
-template <typename T>
+// T = uint16_t (bf16 bits) or float; SUM = false leaves (max, arg max) only and a sum of 0
+template <typename T, bool SUM>
 __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
 {
     constexpr int VEC = 16 / sizeof(T);
@@ -162,7 +166,7 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
 
         if (tid < head) {
             float x[1] = {sizeof(T) == 2 ? bf16_to_f32(((const uint16_t*)base)[v_lo + tid]) : ((const float*)base)[v_lo + tid]};
-            absorb<1>(tr, x, (int)(v_lo + tid));
+            absorb<1, SUM>(tr, x, (int)(v_lo + tid));
         }
         const u32x4* vp = reinterpret_cast<const u32x4*>(base + body0);
         auto widen = [&](const u32x4& raw, float (&x)[VEC]) {
@@ -190,7 +194,7 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
             for (int u = 0; u < UNROLL; ++u) {
                 float x[VEC];
                 widen(raw[u], x);
-                absorb<VEC>(tr, x, (int)(body0 + (i + u * RTHREADS) * VEC));
+                absorb<VEC, SUM>(tr, x, (int)(body0 + (i + u * RTHREADS) * VEC));
             }
         }
         if (i < nvec) {
@@ -204,7 +208,7 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
                 if (i + u * RTHREADS < nvec) {
                     float x[VEC];
                     widen(raw[u], x);
-                    absorb<VEC>(tr, x, (int)(body0 + (i + u * RTHREADS) * VEC));
+                    absorb<VEC, SUM>(tr, x, (int)(body0 + (i + u * RTHREADS) * VEC));
                 }
             }
         }
@@ -212,12 +216,12 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
         if (tid < ntail) {
             float x[1] = {sizeof(T) == 2 ? bf16_to_f32(((const uint16_t*)base)[tail0 + tid]) : ((const float*)base)[tail0 + tid]};
             // tail indices are larger than anything this thread saw before
-            absorb<1>(tr, x, (int)(tail0 + tid));
+            absorb<1, SUM>(tr, x, (int)(tail0 + tid));
         }
     }
 
     // wavefront reduction, then across the 4 wavefronts through LDS
-    Run r = settle(tr);
+    Run r = SUM ? settle(tr) : tr.r;
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
         Run o;
@@ -543,8 +547,8 @@ hipError_t launch_unmask(const fdd_unmask_params& p, const UnmaskPlan& plan, hip
     a.N = p.N; a.B = p.B; a.vsplits = plan.vsplits; a.V = p.V; a.tau = p.tau;
     a.c = 0.f; a.seed_lo = 0u; a.seed_hi = 0u;
     const dim3 grid((unsigned)(plan.vsplits * p.N * p.B));
-    if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_reduce_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
-    else hipLaunchKernelGGL(vocab_reduce_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
+    if (p.dtype == FDD_BF16) hipLaunchKernelGGL((vocab_reduce_kernel<uint16_t, true>), grid, dim3(RTHREADS), 0, s, a);
+    else hipLaunchKernelGGL((vocab_reduce_kernel<float, true>), grid, dim3(RTHREADS), 0, s, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(block_select_kernel, dim3(p.N), dim3(STHREADS), 0, s, a);
@@ -572,8 +576,9 @@ hipError_t launch_verify(const fdd_verify_params& p, const UnmaskPlan& plan, hip
         if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_sample_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
         else hipLaunchKernelGGL(vocab_sample_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
     } else {
-        if (p.dtype == FDD_BF16) hipLaunchKernelGGL(vocab_reduce_kernel<uint16_t>, grid, dim3(RTHREADS), 0, s, a);
-        else hipLaunchKernelGGL(vocab_reduce_kernel<float>, grid, dim3(RTHREADS), 0, s, a);
+        // greedy verifier: step 3 of scaffold speculative decoding compares arg maxima only, so no exponentials
+        if (p.dtype == FDD_BF16) hipLaunchKernelGGL((vocab_reduce_kernel<uint16_t, false>), grid, dim3(RTHREADS), 0, s, a);
+        else hipLaunchKernelGGL((vocab_reduce_kernel<float, false>), grid, dim3(RTHREADS), 0, s, a);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

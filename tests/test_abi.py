@@ -54,8 +54,8 @@ def test_attn_workspace_is_host_arithmetic(lib):
     p1 = attn(splits=1)
     assert lib.fdd_block_attn_workspace(C.byref(p1)) == 0
     p4 = attn(splits=4)
-    # 4 KV heads x 1 M-tile x 4 segments x 256 rows x (128 + 2) floats
-    assert lib.fdd_block_attn_workspace(C.byref(p4)) == 4 * 4 * 256 * 130 * 4
+    # 4 KV heads x 1 M-tile x 4 segments x 256 rows x (128 bf16 averages + (m, l) in fp32)
+    assert lib.fdd_block_attn_workspace(C.byref(p4)) == 4 * 4 * 256 * (128 * 2 + 2 * 4)
     assert lib.fdd_block_attn_workspace(C.byref(attn(Hq=30))) == 0     # invalid -> 0
 
 
