@@ -44,9 +44,11 @@
 //     the vector ALUs reduce the row maximum of tile i, take its exponentials
 //     and round them to bf16.  One wavefront can only issue a vector
 //     instruction every other issue slot, so two wavefronts per SIMD running
-//     this same mix are what fills both pipes.  Tile i+3 is requested at the
-//     start of step i and waits are counted (the loads of a wavefront complete
-//     in issue order), so two tiles stay in flight across a step; LDS
+//     this same mix are what fills both pipes.  V of tile i+3 and K of tile
+//     i+4 are requested at the start of step i (K is read one step before V,
+//     so its slot is free one step earlier) and waits are counted (the loads
+//     of a wavefront complete in issue order), so four half tiles stay in
+//     flight across a step boundary; LDS
 //     fragments are requested two MFMAs before their use.  The loop is
 //     unrolled four times so that ring slots are immediate offsets.
 //   * The softmax reference value of a row is only raised when the running
@@ -90,36 +92,47 @@ constexpr int KT = 64;           // keys per tile
 constexpr int NB = 4;            // ring slots per operand in LDS
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 
+// Kernel arguments.  They are read from memory with scalar loads, a 64-byte line at a time, and every
+// first touch of a line is a round trip of a few hundred nanoseconds: the fields a workgroup needs before
+// it can request its first tiles come first and are pulled in together (see the top of the kernel), the
+// fields of the Q load follow, the rest is only needed while the first tiles are on their way.
 struct Args {
-    const uint16_t* q;
+    // ---- before the first tile request -----------------------------------------------------------
     const uint16_t* pk;
     const uint16_t* pv;
+    const uint16_t* vt;   // packed V^T tiles of the full prefix tiles (PACKED kernels only)
+    long long p_bs, vt_bs;   // batch: element strides between the problems' prefix arrays
+    int W;          // workgroups
+    int per_xcd;    // ceil(W / 8)
+    int S;          // > 0: every M-tile is cut into S equal pieces (W = Hkv*MT*S); 0: free ranges
+    int MT, TPU;    // M-tiles per KV head; units per M-tile = max(TP, 1) + booked private units
+    int base, rem;  // free ranges: U / W and U % W
+    int w_even, w_odd;   // equal pieces: weight of a piece by the parity of the XCD it runs on
+    int Hkv, batch;      // batch: independent problems in this launch
+    int L, TP, TPF;      // prefix rows, prefix tiles, full prefix tiles = L / 64
+    FastDiv dMT, dS, dTPU, dHkv, dPerXcd;   // divisions by launch constants
+    // ---- the Q load ----------------------------------------------------------------------------------
+    const uint16_t* q;
+    const int32_t* qpos;   // stacked rows are the listed block positions only (ascending n*B + b), or nullptr: all of them
+    long long q_bs;
+    int G, R, Hq, NB;      // NB = N * B
+    FastDiv dG;
+    // ---- the rest ------------------------------------------------------------------------------------
     const uint16_t* bk;
     const uint16_t* bv;
+    const uint16_t* ek;   // per-rollout extension [N, Ecap, Hkv, D]
+    const uint16_t* ev;
     uint16_t* out;
     void* ws_o;      // partial averages, bf16, in accumulator order (see the epilogue)
     float* ws_ml;    // partial (m, l) per row
-    const uint16_t* vt;   // packed V^T tiles of the full prefix tiles (PACKED kernels only)
-    const uint16_t* ek;   // per-rollout extension [N, Ecap, Hkv, D]
-    const uint16_t* ev;
+    long long b_bs, e_bs, o_bs;
     int E, Ecap;
-    int batch;            // independent problems in this launch; element strides between their arrays:
-    long long q_bs, p_bs, vt_bs, b_bs, e_bs, o_bs;
-    int N, B, L, Hq, Hkv, G, R, MT, TP;
-    int TPF;        // full prefix tiles = L / 64
-    int TPU;        // units per M-tile = max(TP, 1)
-    int W;          // workgroups
-    int per_xcd;    // ceil(W / 8)
+    int N, B;
     int max_seg;    // partial slots per M-tile
-    int S;          // > 0: every M-tile is cut into S equal pieces (W = Hkv*MT*S); 0: free ranges
-    int base, rem;  // free ranges: U / W and U % W
     int causal;     // in-block keys are visible up to the query's own position only
     float c;        // scale * log2(e)
     int ttpr;       // private tiles per rollout: extension tiles, then block tiles
-    const int32_t* qpos;   // stacked rows are the listed block positions only (ascending n*B + b), or nullptr: all of them
-    int NB;         // N * B
-    FastDiv dMT, dS, dTPU, dHkv, dG, dB, dBG, dTTPR, dBase, dBase1, dPerXcd;   // divisions by launch constants
-    int w_even, w_odd;   // equal pieces: weight of a piece by the parity of the XCD it runs on
+    FastDiv dB, dBG, dTTPR, dBase, dBase1;
 };
 
 template <int D, int WAVES>
@@ -189,6 +202,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
     const int l32 = lane & 31;
     const int half = lane >> 5;
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);   // same value, known to be wave-uniform
+
+    // ---- everything the first tile requests need, in one round trip to the argument block -------
+    {
+        long long h0 = a.p_bs, h1 = a.vt_bs;
+        int h2 = a.W, h3 = a.per_xcd, h4 = a.S, h5 = a.MT, h6 = a.TPU, h7 = a.base, h8 = a.rem, h9 = a.w_even,
+            h10 = a.w_odd, h11 = a.Hkv, h12 = a.batch, h13 = a.L, h14 = a.TP, h15 = a.TPF;
+        uint32_t d0 = a.dMT.mul, d1 = a.dMT.shift, d2 = a.dS.mul, d3 = a.dS.shift, d4 = a.dTPU.mul, d5 = a.dTPU.shift,
+                 d6 = a.dHkv.mul, d7 = a.dHkv.shift, d8 = a.dPerXcd.mul, d9 = a.dPerXcd.shift;
+        const uint16_t *p0 = a.pk, *p1 = a.pv, *p2 = a.vt;
+        asm volatile("" ::"s"(h0), "s"(h1), "s"(h2), "s"(h3), "s"(h4), "s"(h5), "s"(h6), "s"(h7), "s"(h8), "s"(h9), "s"(h10),
+                     "s"(h11), "s"(h12), "s"(h13), "s"(h14), "s"(h15), "s"(d0), "s"(d1), "s"(d2), "s"(d3), "s"(d4), "s"(d5),
+                     "s"(d6), "s"(d7), "s"(d8), "s"(d9), "s"(p0), "s"(p1), "s"(p2));
+    }
 
     // ---- this workgroup's share of the (M-tile, prefix tile) units ------------
     // Workgroups are dealt to the 8 XCDs round-robin by their launch index;
@@ -312,17 +338,20 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         // ---- tile j: global memory -> ring slot j % NB, no registers in between ----
         int issued = 0;
         // full prefix tile (j < F): offsets were prepared once, only the scalar tile offset changes
-        auto fetch_full = [&](int j, uint32_t slot) {     // slot = (j % NB) * T_BYTES, a constant where it matters
+        auto fetch_k = [&](int j, uint32_t slot) {        // slot = (j % NB) * T_BYTES, a constant where it matters
             const uint32_t soff = (uint32_t)((t0 + j) * KT) * stride2 + (uint32_t)(kh * D * 2);
             unsigned char* const kdst = lds + slot + wave_u * (C::NI * 1024);
-            unsigned char* const vdst = kdst + C::V_RING;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(pk_rsrc, (lds_void*)kdst, 16, k_voff[0], soff, 0, 0);
             if (C::NI > 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(pk_rsrc, (lds_void*)(kdst + 1024), 16, k_voff[C::NI - 1], soff, 0, 0);
+        };
+        auto fetch_v = [&](int j, uint32_t slot) {
+            unsigned char* const vdst = lds + slot + wave_u * (C::NI * 1024) + C::V_RING;
             if (PACKED) {
                 const uint32_t voff = (uint32_t)(kh * a.TPF + t0 + j) * C::T_BYTES;
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(pv_rsrc, (lds_void*)vdst, 16, vp_voff, voff, 0, 0);
                 if (C::NI > 1) __builtin_amdgcn_raw_ptr_buffer_load_lds(pv_rsrc, (lds_void*)(vdst + 1024), 16, vp_voff + 1024, voff, 0, 0);
             } else {
+                const uint32_t soff = (uint32_t)((t0 + j) * KT) * stride2 + (uint32_t)(kh * D * 2);
                 int tid_f = tid;
                 FDD_PIN(tid_f);     // recomputed at every fetch rather than kept in registers
 #pragma unroll
@@ -334,9 +363,16 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                 }
             }
         };
+        auto fetch_full = [&](int j, uint32_t slot) {
+            fetch_k(j, slot);
+            fetch_v(j, slot);
+        };
         // The first full tiles are requested before anything else is worked out,
         // so that the rest of the set-up runs under their latency.
+        // (K runs one tile ahead of V: K of tile j is read one step before V of tile j, so its slot is free
+        // one step earlier, and one more half tile per workgroup is on its way at any time)
         for (int j = 0; j < min(NB - 1, F); ++j) fetch_full(j, (uint32_t)j * C::T_BYTES);
+        if (F > NB - 1) fetch_k(NB - 1, (uint32_t)(NB - 1) * C::T_BYTES);
         issued = min(NB - 1, F);
         FDD_SCHED_FENCE();
 
@@ -530,7 +566,7 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             }
 
             // One pipelined step: probabilities and P V of tile i from s_cur while
-            // the scores of tile i+1 go to s_nxt; tile i+3 is requested.
+            // the scores of tile i+1 go to s_nxt; K of tile i+4 and V of tile i+3 are requested.
             //   slots  0- 7  S(i+1) first 32 keys   ||  row maximum of tile i
             //   slots  8-15  S(i+1) second 32 keys  ||  exp of the first 32 keys
             //   slots 16-23  P V first 32 keys      ||  exp of the second 32 keys
@@ -538,16 +574,19 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             // `par` is i % NB as a compile-time constant: ring slots become
             // immediate offsets of the LDS reads.  The scores of tile i+1 are
             // computed whether or not it is a full tile (from whatever its slot
-            // holds); they are only used if it is.  On entry tiles up to i+1 have
-            // landed; on exit tiles up to i+2 have.
+            // holds); they are only used if it is.  On entry K up to tile i+1 and V up
+            // to tile i have landed; on exit K up to tile i+2 and V up to tile i+1.
             auto step = [&](auto par, int i, f32x16 (&s_cur)[2], f32x16 (&s_nxt)[2]) {
                 constexpr int P = decltype(par)::value;
                 constexpr uint32_t KSLOT = (uint32_t)((P + 1) % NB) * C::T_BYTES;
                 constexpr uint32_t VSLOT = (uint32_t)P * C::T_BYTES;
-                // the slot refilled here held tile i-1, last read in the previous step
-                // (masked tiles are requested after the loop: their request code is long)
+                // K of tile i+NB goes where K of tile i was (last read in the previous step, by the scores
+                // computed ahead), V of tile i+NB-1 where V of tile i-1 was
+                // (masked tiles are requested after the loop: their request code is long, and inside the
+                // loop it costs registers the loop does not have: measured, 52..64 vector registers spilled)
+                if (i + NB < F) fetch_k(i + NB, (uint32_t)P * C::T_BYTES);
                 if (i + NB - 1 < F) {
-                    fetch_full(i + NB - 1, (uint32_t)((P + NB - 1) % NB) * C::T_BYTES);
+                    fetch_v(i + NB - 1, (uint32_t)((P + NB - 1) % NB) * C::T_BYTES);
                     issued = i + NB;
                 }
                 auto kfrag = [&](int kb, int ks) {
@@ -644,8 +683,12 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                     o[j % DB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[j % 3], p[2 + j / DB], o[j % DB], 0, 0, 0);
                     FDD_SCHED_FENCE();
                 }
-                // tile i+2 must have landed; the one requested above may still be on its way
-                if (i + 3 < F) wait_vm<C::IPT>(); else wait_vm<0>();
+                // K of tile i+2 and V of tile i+1 must have landed (both requested two steps ago); what this
+                // step and the previous one requested may still be on its way
+                if (i + 4 < F) wait_vm<4 * C::NI>();
+                else if (i + 3 < F) wait_vm<3 * C::NI>();
+                else if (i + 2 < F) wait_vm<C::NI>();
+                else wait_vm<0>();
                 wg_barrier();
             };
             const std::integral_constant<int, 0> r0;
