@@ -6,7 +6,7 @@
 A "step" is one pass of the whole hot path over one batch of synthetic
 input that is already resident in HBM: shared-prefix block attention,
 confidence-threshold unmask over the vocabulary, and the K/V refresh of the
-committed positions; every 8 steps the N rollouts are re-forked from one
+committed positions (done by the unmask call itself); every 8 steps the N rollouts are re-forked from one
 parent block state (a new block starts), which is the fork bookkeeping, and
 the prefix V is laid out once for the attention kernel (fdd_prefix_pack).
 The default workload is the long multi-camera configuration (N=16 rollouts,
@@ -531,10 +531,11 @@ def main():
         if has_unmask:
             if un_pair:
                 un_pair[0].record()
-            F.fdd_unmask_step(logits[i % 2], st["mask"], scaffold, tau, st["tokens"], conf, nun, com, workspace=ws_u)
+            # (the K/V refresh of the committed positions is done by the unmask call's own select kernel)
+            F.fdd_unmask_step(logits[i % 2], st["mask"], scaffold, tau, st["tokens"], conf, nun, com, workspace=ws_u,
+                              refresh=(tk, tv, st["block_k"], st["block_v"]))
             if un_pair:
                 un_pair[1].record()
-            F.fdd_block_kv_update(st["tokens"], com, tk, tv, st["block_k"], st["block_v"])
 
     def sampled(i, i_rel, pairs_a, pairs_u):
         # step i of the block cycle, the i_rel-th step of a sampled stretch: every `stride`-th step carries the
@@ -621,7 +622,7 @@ def main():
         elig0 = int(((d["mask"] == 1) & (d["scaffold_mask"] == 0)).sum())
         st_host = st["mask"].cpu().numpy()
         res["roofline_unmask"] = {
-            "kernel": "vocab_reduce_kernel+block_select_kernel", "bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS,
+            "kernel": "vocab_reduce_kernel+block_select_kernel (with the K/V refresh)", "bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS,
             "avg_call_us": round(un_ms * 1e3, 2), "calls_timed": len(un_samples), "eligible_rows_at_block_start": elig0,
             "eligible_rows_now": int(((st_host == 1) & (d["scaffold_mask"] == 0)).sum()),
         }

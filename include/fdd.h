@@ -193,6 +193,17 @@ typedef struct fdd_unmask_params {
     void *workspace;               /* >= fdd_unmask_workspace() bytes */
     size_t workspace_bytes;
     void *stream;
+    /* Optional K/V refresh of the positions this call commits, done by the same kernel that takes the
+     * commit decisions: exactly what fdd_block_kv_update would do right afterwards with this call's
+     * `tokens` and `committed` (one launch less per denoise step).  All four pointers NULL (and the
+     * sizes 0): no refresh.  Otherwise all four must be given, 16-byte aligned, with a row of
+     * refresh_Hkv * refresh_D elements of refresh_dtype being a multiple of 16 bytes. */
+    const void *refresh_table_k;   /* [refresh_T, refresh_Hkv, refresh_D] */
+    const void *refresh_table_v;
+    void *refresh_block_k;         /* [N, B, refresh_Hkv, refresh_D] in/out */
+    void *refresh_block_v;
+    int32_t refresh_Hkv, refresh_D, refresh_T;
+    int32_t refresh_dtype;         /* fdd_dtype of the tables and the block K/V */
 } fdd_unmask_params;
 
 size_t fdd_unmask_workspace(const fdd_unmask_params *p);

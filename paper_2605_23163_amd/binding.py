@@ -45,7 +45,11 @@ class UnmaskParams(C.Structure):
                 ("logits", C.c_void_p), ("scaffold_mask", C.c_void_p), ("mask", C.c_void_p),
                 ("tokens", C.c_void_p), ("confidences", C.c_void_p), ("n_unmasked", C.c_void_p),
                 ("committed", C.c_void_p), ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
-                ("stream", C.c_void_p)]
+                ("stream", C.c_void_p),
+                ("refresh_table_k", C.c_void_p), ("refresh_table_v", C.c_void_p),
+                ("refresh_block_k", C.c_void_p), ("refresh_block_v", C.c_void_p),
+                ("refresh_Hkv", C.c_int32), ("refresh_D", C.c_int32), ("refresh_T", C.c_int32),
+                ("refresh_dtype", C.c_int32)]
 
 
 class VerifyParams(C.Structure):
@@ -316,9 +320,17 @@ def fdd_block_attn_batched(q, prefix_k, prefix_v, block_k, block_v, out=None, sc
     return out
 
 
-def _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed):
+def _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed, refresh=None):
     N, B, V = logits.shape
     p = UnmaskParams()
+    if refresh is not None:
+        tk, tv, bk, bv = refresh
+        if tuple(bk.shape[:2]) != (N, B) or tk.shape[1:] != bk.shape[2:] or tv.shape != tk.shape or bv.shape != bk.shape:
+            raise TypeError("refresh = (table_k [T,Hkv,D], table_v, block_k [N,B,Hkv,D], block_v)")
+        p.refresh_table_k, p.refresh_table_v = _dev(tk, "table_k"), _dev(tv, "table_v")
+        p.refresh_block_k, p.refresh_block_v = _dev(bk, "block_k"), _dev(bv, "block_v")
+        p.refresh_T, p.refresh_Hkv, p.refresh_D = tk.shape[0], tk.shape[1], tk.shape[2]
+        p.refresh_dtype = _dtype_code(tk)
     p.N, p.B, p.V, p.dtype, p.tau = N, B, V, _dtype_code(logits), float(tau)
     p.logits = _dev(logits, "logits")
     p.scaffold_mask = _dev(scaffold_mask, "scaffold_mask")
@@ -335,8 +347,11 @@ def fdd_unmask_workspace(logits) -> int:
 
 
 def fdd_unmask_step(logits, mask, scaffold_mask, tau, tokens, confidences=None, n_unmasked=None, committed=None,
-                    workspace=None, stream=None):
+                    workspace=None, stream=None, refresh=None):
     """One unmask iteration; ``tokens`` and ``mask`` are updated in place.
+    ``refresh`` = (table_k, table_v, block_k, block_v): the K/V rows of the positions
+    committed by this call are refreshed by the same launch (what
+    ``fdd_block_kv_update`` would do afterwards).
 
     Returns (tokens, confidences, n_unmasked, committed).
     """
@@ -355,7 +370,7 @@ def fdd_unmask_step(logits, mask, scaffold_mask, tau, tokens, confidences=None, 
         n_unmasked = torch.empty((N,), dtype=torch.int32, device=dev)
     if committed is None:
         committed = torch.empty((N, B), dtype=torch.uint8, device=dev)
-    p = _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed)
+    p = _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed, refresh)
     need = lib.fdd_unmask_workspace(C.byref(p))
     ws, nbytes = _workspace(workspace, need, dev)
     p.workspace = ws.data_ptr() if ws is not None else None
@@ -365,13 +380,14 @@ def fdd_unmask_step(logits, mask, scaffold_mask, tau, tokens, confidences=None, 
     return tokens, confidences, n_unmasked, committed
 
 
-def fdd_unmask_step_static(logits, mask, scaffold_mask, tau, tokens, confidences, n_unmasked, committed, stream=None):
+def fdd_unmask_step_static(logits, mask, scaffold_mask, tau, tokens, confidences, n_unmasked, committed, stream=None,
+                           refresh=None):
     """``fdd_unmask_step`` without a workspace and without any allocation: every
     output tensor is the caller's, the partial results live in the library's
     built-in device array.  Raises FddError when the shape needs more than that
     array holds."""
     lib = load_library()
-    p = _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed)
+    p = _unmask_params(logits, mask, scaffold_mask, tokens, tau, confidences, n_unmasked, committed, refresh)
     p.workspace = None
     p.workspace_bytes = 0
     p.stream = _stream_ptr(stream)

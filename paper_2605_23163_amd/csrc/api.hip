@@ -229,6 +229,18 @@ fdd_status fdd::check_unmask_args(const fdd_unmask_params* p, const char* fn)
     if (!p->logits || !p->mask || !p->tokens || !p->confidences)
         return fail(FDD_ERR_NULL, "%s: logits, mask, tokens and confidences must not be NULL", fn);
     if (!aligned16(p->logits)) return fail(FDD_ERR_UNSUPPORTED, "%s: logits must be 16-byte aligned", fn);
+    if (p->refresh_table_k || p->refresh_table_v || p->refresh_block_k || p->refresh_block_v) {
+        if (!p->refresh_table_k || !p->refresh_table_v || !p->refresh_block_k || !p->refresh_block_v)
+            return fail(FDD_ERR_NULL, "%s: the K/V refresh needs refresh_table_k, refresh_table_v, refresh_block_k and refresh_block_v", fn);
+        if (p->refresh_Hkv <= 0 || p->refresh_D <= 0 || p->refresh_T <= 0)
+            return fail(FDD_ERR_SHAPE, "%s: refresh_Hkv, refresh_D, refresh_T must be positive", fn);
+        if (p->refresh_dtype != FDD_F32 && p->refresh_dtype != FDD_BF16)
+            return fail(FDD_ERR_DTYPE, "%s: refresh_dtype %d is neither FDD_F32 nor FDD_BF16", fn, p->refresh_dtype);
+        const long long row = (long long)p->refresh_Hkv * p->refresh_D * (p->refresh_dtype == FDD_BF16 ? 2 : 4);
+        if (row % 16 || row > (1ll << 24)) return fail(FDD_ERR_UNSUPPORTED, "%s: a refreshed K/V row must be a multiple of 16 bytes (and at most 16 MiB)", fn);
+        if (!aligned16(p->refresh_table_k) || !aligned16(p->refresh_table_v) || !aligned16(p->refresh_block_k) || !aligned16(p->refresh_block_v))
+            return fail(FDD_ERR_UNSUPPORTED, "%s: refresh tables and block K/V must be 16-byte aligned", fn);
+    }
     return FDD_OK;
 }
 

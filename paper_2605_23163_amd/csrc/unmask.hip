@@ -55,6 +55,12 @@ struct Args {
     uint8_t* committed;
     Partial* ws;
     const int32_t* draft;   // verify pass only
+    // K/V refresh of the committed positions (unmask step only): row (token mod T) of the tables, or no refresh
+    const u32x4* rf_tk;
+    const u32x4* rf_tv;
+    u32x4* rf_bk;
+    u32x4* rf_bv;
+    int rf_T, rf_row_vecs;  // table rows; 16-byte pieces per K/V row (0: no refresh)
     int N, B, vsplits;
     long long V;
     float tau;
@@ -412,16 +418,28 @@ __global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
     int best_b = 0x7fffffff;
     int best_tok = -1;
 
-    for (int b = tid; b < a.B; b += STHREADS) {
-        const size_t i = (size_t)n * a.B + b;
-        const bool eligible = a.mask[i] == 1 && !(a.scaffold && a.scaffold[i]);
+    // the wavefront refreshes the K/V row of position i, which now holds token `tok` (see fdd_block_kv_update)
+    auto refresh_row = [&](size_t i, int tok) {
+        int t = tok % a.rf_T;
+        if (t < 0) t += a.rf_T;
+        for (int c = tid; c < a.rf_row_vecs; c += STHREADS) {
+            a.rf_bk[i * a.rf_row_vecs + c] = a.rf_tk[(size_t)t * a.rf_row_vecs + c];
+            a.rf_bv[i * a.rf_row_vecs + c] = a.rf_tv[(size_t)t * a.rf_row_vecs + c];
+        }
+    };
+
+    for (int b0 = 0; b0 < a.B; b0 += STHREADS) {     // lane `tid` takes position b0 + tid (ascending per lane)
+        const int b = b0 + tid;
+        const size_t i = (size_t)n * a.B + (b < a.B ? b : 0);
+        const bool eligible = b < a.B && a.mask[i] == 1 && !(a.scaffold && a.scaffold[i]);
         float conf_out = -INFINITY;
         uint8_t com = 0;
+        int arg = -1;
         if (eligible) {
             const Partial* p = a.ws + i * a.vsplits;
             // pieces cover ascending index ranges: strict '>' keeps the lowest id
             float M = p[0].m;
-            int arg = p[0].arg;
+            arg = p[0].arg;
             for (int s = 1; s < a.vsplits; ++s)
                 if (p[s].m > M) { M = p[s].m; arg = p[s].arg; }
             // sum of the pieces' fp32 sums, rescaled to the row maximum, finished in fp64
@@ -438,8 +456,18 @@ __global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
             }
             if (conf > best_conf) { best_conf = conf; best_b = b; best_tok = arg; }   // ascending b per thread
         }
-        a.conf[i] = conf_out;
-        if (a.committed) a.committed[i] = com;
+        if (b < a.B) {
+            a.conf[i] = conf_out;
+            if (a.committed) a.committed[i] = com;
+        }
+        if (a.rf_row_vecs > 0) {
+            unsigned long long m = __ballot(com != 0);
+            while (m) {
+                const int j = __ffsll((long long)m) - 1;
+                m &= m - 1;
+                refresh_row((size_t)n * a.B + b0 + j, __shfl(arg, j, 64));
+            }
+        }
     }
     // wavefront reduction: commits are summed; the best candidate is the one of
     // highest confidence, lowest position on ties
@@ -451,17 +479,19 @@ __global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
         const int ot = __shfl_xor(best_tok, off, 64);
         if (oc > best_conf || (oc == best_conf && ob < best_b)) { best_conf = oc; best_b = ob; best_tok = ot; }
     }
-    if (tid == 0) {
-        if (count == 0 && best_tok >= 0) {
-            // nothing reached tau: commit the most confident eligible position
-            const size_t i = (size_t)n * a.B + best_b;
+    // (count and the best candidate are now the same in every lane)
+    if (count == 0 && best_tok >= 0) {
+        // nothing reached tau: commit the most confident eligible position
+        const size_t i = (size_t)n * a.B + best_b;
+        if (tid == 0) {
             a.tokens[i] = best_tok;
             a.mask[i] = 0;
             if (a.committed) a.committed[i] = 1;
-            count = 1;
         }
-        if (a.n_unmasked) a.n_unmasked[n] = count;
+        if (a.rf_row_vecs > 0) refresh_row(i, best_tok);
+        count = 1;
     }
+    if (tid == 0 && a.n_unmasked) a.n_unmasked[n] = count;
 }
 
 // Accept scan of scaffold speculative decoding: one wavefront per rollout.
@@ -544,6 +574,12 @@ hipError_t launch_unmask(const fdd_unmask_params& p, const UnmaskPlan& plan, hip
     a.committed = p.committed;
     a.ws = static_cast<Partial*>(p.workspace);
     a.draft = nullptr;
+    a.rf_tk = static_cast<const u32x4*>(p.refresh_table_k);
+    a.rf_tv = static_cast<const u32x4*>(p.refresh_table_v);
+    a.rf_bk = static_cast<u32x4*>(p.refresh_block_k);
+    a.rf_bv = static_cast<u32x4*>(p.refresh_block_v);
+    a.rf_T = p.refresh_T;
+    a.rf_row_vecs = p.refresh_block_k ? (int)((size_t)p.refresh_Hkv * p.refresh_D * (p.refresh_dtype == FDD_BF16 ? 2 : 4) / 16) : 0;
     a.N = p.N; a.B = p.B; a.vsplits = plan.vsplits; a.V = p.V; a.tau = p.tau;
     a.c = 0.f; a.seed_lo = 0u; a.seed_hi = 0u;
     const dim3 grid((unsigned)(plan.vsplits * p.N * p.B));
@@ -567,6 +603,7 @@ hipError_t launch_verify(const fdd_verify_params& p, const UnmaskPlan& plan, hip
     a.committed = p.accepted;
     a.ws = static_cast<Partial*>(p.workspace);
     a.draft = p.draft;
+    a.rf_tk = nullptr; a.rf_tv = nullptr; a.rf_bk = nullptr; a.rf_bv = nullptr; a.rf_T = 0; a.rf_row_vecs = 0;
     a.N = p.N; a.B = p.B; a.vsplits = plan.vsplits; a.V = p.V; a.tau = 0.f;
     a.c = p.temperature > 0.f ? (float)(1.4426950408889634 / (double)p.temperature) : 0.f;
     a.seed_lo = (uint32_t)p.seed;

@@ -91,6 +91,14 @@ def test_unmask_workspace_and_errors(lib):
         assert lib.fdd_unmask_step(C.byref(unmask(**kw))) == code, kw
         assert lib.fdd_last_error().decode().startswith("fdd_unmask_step:")
     assert lib.fdd_unmask_step(None) == 1
+    # the optional K/V refresh: all four arrays or none, sane row shape, aligned
+    ok = dict(refresh_table_k=512, refresh_table_v=1024, refresh_block_k=2048, refresh_block_v=4096, refresh_Hkv=4,
+              refresh_D=128, refresh_T=16, refresh_dtype=bd.FDD_BF16)
+    for kw, code in [(dict(refresh_table_v=None), 1), (dict(refresh_block_k=None), 1), (dict(refresh_T=0), 2),
+                     (dict(refresh_Hkv=-1), 2), (dict(refresh_dtype=9), 3), (dict(refresh_D=3), 4),
+                     (dict(refresh_block_v=4100), 4)]:
+        assert lib.fdd_unmask_step(C.byref(unmask(**{**ok, **kw}))) == code, kw
+        assert lib.fdd_unmask_step_static(C.byref(unmask(**{**ok, **kw}))) == code, kw
 
 
 def test_prefix_pack_sizes_and_errors(lib):

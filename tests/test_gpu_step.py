@@ -37,8 +37,12 @@ def test_multi_step_denoise_matches_oracle(oracle):
         o["block_k"], o["block_v"] = oracle.block_kv_update(o["tokens"], r["committed"], d["table_k"], d["table_v"],
                                                             o["block_k"], o["block_v"])
         out = F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], g["block_k"], g["block_v"], g["scaffold"])
-        _, conf, nun, com = F.fdd_unmask_step(to_dev(logits), g["mask"], g["scaffold"], tau, g["tokens"])
-        F.fdd_block_kv_update(g["tokens"], com, g["table_k"], g["table_v"], g["block_k"], g["block_v"])
+        if step % 2 == 0:
+            _, conf, nun, com = F.fdd_unmask_step(to_dev(logits), g["mask"], g["scaffold"], tau, g["tokens"])
+            F.fdd_block_kv_update(g["tokens"], com, g["table_k"], g["table_v"], g["block_k"], g["block_v"])
+        else:       # the same refresh done by the unmask call itself
+            _, conf, nun, com = F.fdd_unmask_step(to_dev(logits), g["mask"], g["scaffold"], tau, g["tokens"],
+                                                  refresh=(g["table_k"], g["table_v"], g["block_k"], g["block_v"]))
         torch.cuda.synchronize()
         err = np.abs(to_f64(out) - ref_out).max()
         assert err <= 2e-2, f"step {step}: attention max-abs {err}"
@@ -85,8 +89,9 @@ def test_config5_two_steps_in_the_bench_configuration(oracle):
             ws_u = torch.empty(max(256, F.fdd_unmask_workspace(tl)), dtype=torch.uint8, device="cuda")
         F.fdd_block_attn(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"], st["block_v"], scaffold, out=out,
                          workspace=ws_a, prefix_v_packed=packed)
-        F.fdd_unmask_step(tl, st["mask"], scaffold, tau, st["tokens"], conf, nun, com, workspace=ws_u)
-        F.fdd_block_kv_update(st["tokens"], com, g["table_k"], g["table_v"], st["block_k"], st["block_v"])
+        # (the K/V refresh of the committed positions rides on the unmask call, as in bench.py)
+        F.fdd_unmask_step(tl, st["mask"], scaffold, tau, st["tokens"], conf, nun, com, workspace=ws_u,
+                          refresh=(g["table_k"], g["table_v"], st["block_k"], st["block_v"]))
         torch.cuda.synchronize()
         # every output row of the step against the oracle
         ref = oracle.block_attn(d["q"], d["prefix_k"], d["prefix_v"], o["block_k"], o["block_v"])

@@ -271,3 +271,29 @@ def test_kv_update_and_fork(F, oracle, dtype):
         got = F.fdd_fork_block(to_dev(src), 6)
         torch.cuda.synchronize()
         assert torch.equal(got, to_dev(want))
+
+
+@pytest.mark.parametrize("dtype", [W.BF16, W.F32])
+@pytest.mark.parametrize("tau", [0.0, 0.6, 1.5])
+def test_refresh_inside_the_unmask_call_equals_the_separate_update(F, oracle, dtype, tau):
+    # many commits per block (tau = 0), some (tau = 0.6) and the forced single commit (tau > 1); B > 64 so that a
+    # wavefront walks more than one chunk of positions
+    print_case(test="unmask_fused_refresh", dtype=dtype, tau=tau)
+    rng = np.random.default_rng(41)
+    N, B, V, Hkv, D, T = 3, 70, 777, 2, 64, 50
+    logits, mask, scaffold, tokens = synth(rng, N, B, V, dtype, 1.0, 9.0, 0.5, 0.3, 0.8)
+    f = lambda *s: W.to_storage(rng.standard_normal(s).astype(np.float32), dtype)
+    tk, tv, bk, bv = f(T, Hkv, D), f(T, Hkv, D), f(N, B, Hkv, D), f(N, B, Hkv, D)
+    t32 = tau32(tau)
+    ref = oracle.unmask_step(logits, mask, scaffold, tokens, t32)
+    assert not (((mask == 1) & (scaffold == 0)) & (np.abs(ref["confidences"] - t32) < 1e-3)).any()
+    rk, rv = oracle.block_kv_update(ref["tokens"], ref["committed"], tk, tv, bk, bv)
+    m, t = torch.from_numpy(mask.copy()).cuda(), torch.from_numpy(tokens.copy()).cuda()
+    gk, gv = to_dev(bk), to_dev(bv)
+    _, conf, nun, com = F.fdd_unmask_step(to_dev(logits), m, torch.from_numpy(scaffold).cuda(), t32, t,
+                                          refresh=(to_dev(tk), to_dev(tv), gk, gv))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(t.cpu().numpy(), ref["tokens"])
+    np.testing.assert_array_equal(com.cpu().numpy(), ref["committed"])
+    assert torch.equal(gk, to_dev(rk)) and torch.equal(gv, to_dev(rv))
+    assert int(ref["committed"].sum()) >= N
