@@ -214,6 +214,17 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         asm volatile("" ::"s"(h0), "s"(h1), "s"(h2), "s"(h3), "s"(h4), "s"(h5), "s"(h6), "s"(h7), "s"(h8), "s"(h9), "s"(h10),
                      "s"(h11), "s"(h12), "s"(h13), "s"(h14), "s"(h15), "s"(d0), "s"(d1), "s"(d2), "s"(d3), "s"(d4), "s"(d5),
                      "s"(d6), "s"(d7), "s"(d8), "s"(d9), "s"(p0), "s"(p1), "s"(p2));
+        // the fields of the Q load, and a first touch of every other 64-byte line of the block (what is read
+        // from those later then comes from the scalar cache)
+        const uint16_t* q0 = a.q;
+        const int32_t* q1 = a.qpos;
+        long long q2 = a.q_bs;
+        int q3 = a.G, q4 = a.R, q5 = a.Hq, q6 = a.NB;
+        uint32_t q7 = a.dG.mul, q8 = a.dG.shift;
+        const uint32_t* ap = reinterpret_cast<const uint32_t*>(&a);
+        static_assert(sizeof(Args) > 80 * 4 && sizeof(Args) <= 96 * 4, "one touch per 64-byte line of Args");
+        uint32_t t3 = ap[48], t4 = ap[64], t5 = ap[80];
+        asm volatile("" ::"s"(q0), "s"(q1), "s"(q2), "s"(q3), "s"(q4), "s"(q5), "s"(q6), "s"(q7), "s"(q8), "s"(t3), "s"(t4), "s"(t5));
     }
 
     // ---- this workgroup's share of the (M-tile, prefix tile) units ------------
@@ -367,15 +378,6 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
             fetch_k(j, slot);
             fetch_v(j, slot);
         };
-        // The first full tiles are requested before anything else is worked out,
-        // so that the rest of the set-up runs under their latency.
-        // (K runs one tile ahead of V: K of tile j is read one step before V of tile j, so its slot is free
-        // one step earlier, and one more half tile per workgroup is on its way at any time)
-        for (int j = 0; j < min(NB - 1, F); ++j) fetch_full(j, (uint32_t)j * C::T_BYTES);
-        if (F > NB - 1) fetch_k(NB - 1, (uint32_t)(NB - 1) * C::T_BYTES);
-        issued = min(NB - 1, F);
-        FDD_SCHED_FENCE();
-
         // ---- Q fragments: B operand of S^T = K Q^T ------------------------------
         const int row0_wg = mt * MROWS;
         const int row0 = row0_wg + wave * 32;
@@ -395,6 +397,27 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
                 qf[ks] = __builtin_bit_cast(bf16x8, raw);
             }
         }
+        FDD_SCHED_FENCE();
+
+        // Q is requested first and the first full tiles right after it, before anything else is worked
+        // out, so that the rest of the set-up runs under their latency.  The loads of a wavefront complete
+        // in issue order: with Q in front, the first step can start as soon as Q and the first tiles are
+        // there, while the later ones are still on their way.
+        // (K runs one tile ahead of V: K of tile j is read one step before V of tile j, so its slot is free
+        // one step earlier, and one more half tile per workgroup is on its way at any time)
+        // The seven requests are issued without a branch, whatever F is: a segment with fewer than four full
+        // tiles requests its last full tile again (same addresses, served by the caches; a segment with none
+        // requests the last full tile of the prefix, and a prefix shorter than a tile is cut off by the buffer bounds),
+        // into slots whose later contents arrive later.  Only so does the compiler know that these requests
+        // follow the Q loads on every path and lets the wait for Q pass while they are in flight.
+        {
+            const int jmax = max(F - 1, 0);
+            const int jcap = max(a.TPF - 1, 0) - t0;     // keeps t0 + j inside the full tiles (it may be negative)
+#pragma unroll
+            for (int j = 0; j < NB - 1; ++j) fetch_full(min(min(j, jmax), jcap), (uint32_t)j * C::T_BYTES);
+            fetch_k(min(min(NB - 1, jmax), jcap), (uint32_t)(NB - 1) * C::T_BYTES);
+        }
+        issued = min(NB - 1, F);
         FDD_SCHED_FENCE();
 
         // ---- the rest of the set-up ------------------------------------------------
@@ -549,8 +572,9 @@ __global__ __launch_bounds__(WAVES * 64) void attn_bf16_kernel(Args a)
         bf16x8 p[4];      // probabilities of a tile as MFMA B operands, one per 16-key step
 
         // ---- full prefix tiles, software pipelined ---------------------------------
-        // (all of it: the Q loads sit between the tile requests in issue order)
-        wait_vm<0>();
+        // Issue order so far: Q, then K0 V0 K1 V1 K2 V2 K3.  The first step needs Q, K0, V0 and K1; with four
+        // full tiles or more nothing else has been requested, and the last four half tiles may stay in flight.
+        if (F >= NB) wait_vm<4 * C::NI>(); else wait_vm<0>();
         wg_barrier();
         landed = issued - 1;
         if (F > 0) {
