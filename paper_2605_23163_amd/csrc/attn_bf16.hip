@@ -924,20 +924,36 @@ __global__ __launch_bounds__(256) void attn_merge_bf16_kernel(MergeArgs a)
     const int row0 = mt * 256 + wave * 32;    // first stacked row of the block's 32 rows
     if (row0 >= a.R) return;
 
+    // ---- this thread's chunk; the first four segments' averages are requested before anything else, so that
+    // their latency and that of the (m, l) pairs below overlap ------------------------------------
+    const int sg = tid / CPB, cl = tid - sg * CPB;
+    const int cidx = c0 + cl;                          // chunk inside the M-tile: [wave][register pair][lane]
+    const int lane = cidx & 63, i2 = (cidx >> 6) % (2 * DB);
+    const int r = lane & 31, half = lane >> 5;
+    const bool live = row0 + r < a.R;
+    const u32x4* src = a.ws_o + ((size_t)M * a.max_seg) * CH + cidx;
+    u32x4 x[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int s = sg + u * a.SG;
+        x[u] = u32x4{0u, 0u, 0u, 0u};
+        if (live && s < n_seg) x[u] = src[(size_t)s * CH];
+    }
+
     // ---- weights of the segments, per row: 8 threads per row ----------------------------------
     float* const W = smem;                            // [32][n_seg]
     {
-        const int r = tid >> 3, j = tid & 7;
-        const bool live = row0 + r < a.R;
-        const float* ml = a.ws_ml + (((size_t)M * a.max_seg) * 256 + wave * 32 + r) * 2;
+        const int rr = tid >> 3, j = tid & 7;
+        const bool live_r = row0 + rr < a.R;
+        const float* ml = a.ws_ml + (((size_t)M * a.max_seg) * 256 + wave * 32 + rr) * 2;
         float mx = -INFINITY;
         for (int s = j; s < n_seg; s += 8) {
-            float2 x = make_float2(-INFINITY, 0.f);
-            if (live) x = *reinterpret_cast<const float2*>(ml + (size_t)s * 512);
-            if (!(x.y > 0.f)) x.x = -INFINITY;        // a segment that saw no key of this row
-            W[r * n_seg + s] = x.x;
-            smem[32 * n_seg + r * n_seg + s] = x.y;
-            mx = fmaxf(mx, x.x);
+            float2 y = make_float2(-INFINITY, 0.f);
+            if (live_r) y = *reinterpret_cast<const float2*>(ml + (size_t)s * 512);
+            if (!(y.y > 0.f)) y.x = -INFINITY;        // a segment that saw no key of this row
+            W[rr * n_seg + s] = y.x;
+            smem[32 * n_seg + rr * n_seg + s] = y.y;
+            mx = fmaxf(mx, y.x);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 1, 64));
         mx = fmaxf(mx, __shfl_xor(mx, 2, 64));
@@ -945,41 +961,37 @@ __global__ __launch_bounds__(256) void attn_merge_bf16_kernel(MergeArgs a)
         const float mref = mx == -INFINITY ? 0.f : mx;
         float sum = 0.f;
         for (int s = j; s < n_seg; s += 8) {
-            const float w = smem[32 * n_seg + r * n_seg + s] * exp2f((W[r * n_seg + s] - mref) * a.c);
-            W[r * n_seg + s] = w;
+            const float w = smem[32 * n_seg + rr * n_seg + s] * exp2f((W[rr * n_seg + s] - mref) * a.c);
+            W[rr * n_seg + s] = w;
             sum += w;
         }
         sum += __shfl_xor(sum, 1, 64);
         sum += __shfl_xor(sum, 2, 64);
         sum += __shfl_xor(sum, 4, 64);
         const float inv = sum > 0.f ? 1.f / sum : 0.f;
-        for (int s = j; s < n_seg; s += 8) W[r * n_seg + s] *= inv;
+        for (int s = j; s < n_seg; s += 8) W[rr * n_seg + s] *= inv;
     }
     __syncthreads();
 
     // ---- weighted sum of the segments' averages -------------------------------------------------
-    const int sg = tid / CPB, cl = tid - sg * CPB;
-    const int cidx = c0 + cl;                          // chunk inside the M-tile: [wave][register pair][lane]
-    const int lane = cidx & 63, i2 = (cidx >> 6) % (2 * DB);
-    const int r = lane & 31, half = lane >> 5;
-    const bool live = row0 + r < a.R;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     if (live) {
-        const u32x4* src = a.ws_o + ((size_t)M * a.max_seg) * CH + cidx;
         for (int s0 = sg; s0 < n_seg; s0 += 4 * a.SG) {
-            u32x4 x[4];
+            // the next four segments of this thread are requested before the current four are summed
+            u32x4 nx[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + (4 + u) * a.SG;
+                nx[u] = u32x4{0u, 0u, 0u, 0u};
+                if (s < n_seg) nx[u] = src[(size_t)s * CH];
+            }
             float w[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const int s = s0 + u * a.SG;
-                w[u] = 0.f;
-                x[u] = u32x4{0u, 0u, 0u, 0u};
-                if (s < n_seg) {
-                    x[u] = src[(size_t)s * CH];
-                    w[u] = W[r * n_seg + s];
-                }
+                w[u] = s < n_seg ? W[r * n_seg + s] : 0.f;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
@@ -989,6 +1001,8 @@ __global__ __launch_bounds__(256) void attn_merge_bf16_kernel(MergeArgs a)
                     acc[2 * j] = fmaf(__uint_as_float(x[u][j] << 16), w[u], acc[2 * j]);
                     acc[2 * j + 1] = fmaf(__uint_as_float(x[u][j] & 0xffff0000u), w[u], acc[2 * j + 1]);
                 }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x[u] = nx[u];
         }
     }
     if (a.SG > 1) {
