@@ -95,9 +95,10 @@ class Events:
         return float(np.mean([a.elapsed_time(b) for a, b in self.pairs[:used]]))
 
 
-def time_attention_only(F, w, steps, warmup, n_buffers):
+def time_attention_only(F, w, steps, warmup, n_buffers, prepacked=False):
     """Attention alone on `n_buffers` distinct prefix buffers used in rotation
-    (cold caches when their total size exceeds the 256 MB last-level cache)."""
+    (cold caches when their total size exceeds the 256 MB last-level cache).
+    `prepacked`: the caller has laid the prefix V out beforehand (fdd_prefix_pack)."""
     import torch
     import fdd_workloads as W
     d = W.attention_inputs(w)
@@ -105,20 +106,23 @@ def time_attention_only(F, w, steps, warmup, n_buffers):
     pk0, pv0 = dev(d["prefix_k"]), dev(d["prefix_v"])
     pks = [pk0] + [pk0.clone() for _ in range(n_buffers - 1)]
     pvs = [pv0] + [pv0.clone() for _ in range(n_buffers - 1)]
+    packs = [F.fdd_prefix_pack(v) if prepacked else None for v in pvs]
     out = torch.empty_like(q)
-    ws_bytes = F.fdd_block_attn_workspace(q, pk0, pv0, bk, bv)
+    ws_bytes = F.fdd_block_attn_workspace(q, pk0, pv0, bk, bv, prefix_v_packed=packs[0])
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
     n_ev = (steps + EVENT_STRIDE - 1) // EVENT_STRIDE       # the kernel is timed on a sample of the calls (see main)
     ev = Events(n_ev)
     for i in range(warmup):
-        F.fdd_block_attn(q, pks[i % n_buffers], pvs[i % n_buffers], bk, bv, out=out, workspace=ws)
+        F.fdd_block_attn(q, pks[i % n_buffers], pvs[i % n_buffers], bk, bv, out=out, workspace=ws,
+                         prefix_v_packed=packs[i % n_buffers])
     torch.cuda.synchronize()
     t0 = torch.cuda.Event(enable_timing=True)
     t1 = torch.cuda.Event(enable_timing=True)
     t0.record()
     for i in range(steps):
         F.fdd_profile_attn_events(*(ev.pairs[i // EVENT_STRIDE] if i % EVENT_STRIDE == 0 else (None, None)))
-        F.fdd_block_attn(q, pks[i % n_buffers], pvs[i % n_buffers], bk, bv, out=out, workspace=ws)
+        F.fdd_block_attn(q, pks[i % n_buffers], pvs[i % n_buffers], bk, bv, out=out, workspace=ws,
+                         prefix_v_packed=packs[i % n_buffers])
     t1.record()
     torch.cuda.synchronize()
     F.fdd_profile_attn_events(None, None)
@@ -126,13 +130,17 @@ def time_attention_only(F, w, steps, warmup, n_buffers):
     kern_ms = ev.mean_ms(n_ev)
     prefix, total = attn_bytes(w)
     return {
-        "workload": f"N={w.N} B={w.B} L={w.L} Hq={w.Hq} Hkv={w.Hkv} D={w.D} bf16, {n_buffers} rotating prefix buffers",
+        "workload": f"N={w.N} B={w.B} L={w.L} Hq={w.Hq} Hkv={w.Hkv} D={w.D} bf16, {n_buffers} rotating prefix buffers"
+                    + (", prefix V laid out beforehand" if prepacked else ""),
         "call_us": round(call_ms * 1e3, 2), "kernel_us": round(kern_ms * 1e3, 2),
         "prefix_bytes": prefix, "prefix_GBs_kernel": round(prefix / (kern_ms * 1e-3) / 1e9, 1),
         "prefix_GBs_call": round(prefix / (call_ms * 1e-3) / 1e9, 1),
         "frac_peak_hbm_kernel": round(prefix / (kern_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "frac_peak_hbm_call": round(prefix / (call_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
         "rollout_tokens_per_s": round(w.N * w.B / (call_ms * 1e-3), 1),
         "tflops_kernel": round(attn_flops(w) / (kern_ms * 1e-3) / 1e12, 1),
+        "frac_peak_mfma_kernel": round(attn_flops(w) / (kern_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "frac_peak_mfma_call": round(attn_flops(w) / (call_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
     }
 
 
@@ -448,6 +456,7 @@ def main():
                     help="run only the N=1 layer sweeps (for profiling them) and print their figures")
     ap.add_argument("--attn-only", default=None, metavar="WORKLOAD",
                     help="run only the attention call of this workload (cfg2, cfg3, n1_L16384) for profiling it")
+    ap.add_argument("--prepacked", action="store_true", help="with --attn-only: lay the prefix V out beforehand")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="run only a device copy of this many MiB, five times (calibration of the HBM byte counters)")
     args = ap.parse_args()
@@ -471,7 +480,8 @@ def main():
         wl["n1_L16384"] = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
         wa = wl[args.attn_only]
         nbuf = max(1, int(600e6 // attn_bytes(wa)[0]))      # rotate over more than the last-level cache holds
-        print(json.dumps({args.attn_only: time_attention_only(F, wa, args.steps, args.warmup, min(nbuf, 128))}))
+        print(json.dumps({args.attn_only: time_attention_only(F, wa, args.steps, args.warmup, min(nbuf, 128),
+                                                              prepacked=args.prepacked)}))
         return
     if args.n1_only:
         n1 = W.CONFIGS["cfg2"]
@@ -641,6 +651,8 @@ def main():
         res["n1_prefix_stream_warm"] = time_attention_only(F, n1, 200, 20, 1)      # one buffer: served from the caches
         n1_long = W.Workload("n1_L16384", N=1, B=32, L=16384, Hq=28, Hkv=4, D=128, dtype=W.BF16, seed=12)
         res["n1_prefix_stream_L16384"] = time_attention_only(F, n1_long, 200, 20, 20)
+        res["cfg3_attention"] = time_attention_only(F, W.CONFIGS["cfg3"], 200, 40, 40, prepacked=True)
+        res["cfg3_attention_plain_call"] = time_attention_only(F, W.CONFIGS["cfg3"], 200, 40, 40)
         res["n1_layer_sweep"] = time_layer_sweep_graph(F, n1, 28, 20)
         res["n1_layer_sweep_L16384"] = time_layer_sweep_graph(F, n1_long, 28, 10)
         res["n1_batched"] = time_batched(F, n1, 28, 50)

@@ -195,10 +195,12 @@ bool make_attn_plan(const fdd_attn_params& p, AttnPlan* plan)
         pl.ws_o_bytes = 0;
         pl.ws_ml_bytes = 0;
     }
-    // V is repacked once per call when more than one M-tile streams every V tile
-    // (or taken ready-made from the caller)
+    // The kernel reads V repacked when the caller brings it that way (fdd_prefix_pack, once per prefix).
+    // Repacking inside the call is a launch and a pass over V of its own, and the kernel that reads V as it
+    // lies (transposing LDS reads) is only about 2.5 % slower: measured, the in-call pass pays from about
+    // the size of N=16, B=64, L=16384 on (28 M-tiles x 256 tiles per KV head), and costs 3..5 us below it.
     pl.ws_vt_bytes = 0;
-    pl.packed = p.dtype == FDD_BF16 && p.L >= pl.key_tile && (pl.MT >= 2 || p.prefix_v_packed);
+    pl.packed = p.dtype == FDD_BF16 && p.L >= pl.key_tile && (p.prefix_v_packed || (long long)pl.MT * pl.TP >= 8192);
     if (pl.packed && !p.prefix_v_packed)
         pl.ws_vt_bytes = (((size_t)p.Hkv * batch * (p.L / pl.key_tile) * pl.key_tile * p.D * 2) + 255) & ~(size_t)255;
     *plan = pl;
