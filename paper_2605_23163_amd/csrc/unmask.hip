@@ -140,14 +140,27 @@ __device__ __forceinline__ Run settle(const ThreadRun& t)
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 
+// Workgroups are dealt to the 8 XCDs round-robin by launch index, and a workgroup whose row is
+// not eligible leaves at once.  With (row, piece) = (index / vsplits, index % vsplits) an XCD
+// would always get rows of the same residue, and a scaffold pattern that repeats from rollout
+// to rollout (it does: the schema is shared) would load the XCDs unequally.  So each group of 8
+// consecutive indices is rotated by its own number: over the groups every XCD meets every residue.
+__device__ __forceinline__ unsigned unit_of_workgroup()
+{
+    const unsigned u = blockIdx.x, g = u >> 3;
+    if ((g << 3) + 8u > gridDim.x) return u;           // a last, incomplete group stays as it is
+    return (g << 3) + ((u + g) & 7u);
+}
+
 // T = uint16_t (bf16 bits) or float; SUM = false leaves (max, arg max) only and a sum of 0
 template <typename T, bool SUM>
 __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
 {
     constexpr int VEC = 16 / sizeof(T);
-    const int row = blockIdx.x / a.vsplits;
+    const unsigned unit = unit_of_workgroup();
+    const int row = unit / a.vsplits;
     if (a.mask[row] != 1 || (a.scaffold && a.scaffold[row])) return;
-    const int piece = blockIdx.x % a.vsplits;
+    const int piece = unit % a.vsplits;
     const long long per = (a.V + a.vsplits - 1) / a.vsplits;
     const long long v_lo = piece * per;
     const long long v_hi = min(a.V, v_lo + per);
@@ -318,9 +331,10 @@ template <typename T>
 __global__ __launch_bounds__(RTHREADS) void vocab_sample_kernel(Args a)
 {
     constexpr int VEC = 16 / sizeof(T);
-    const int row = blockIdx.x / a.vsplits;
+    const unsigned unit = unit_of_workgroup();
+    const int row = unit / a.vsplits;
     if (a.mask[row] != 1 || (a.scaffold && a.scaffold[row])) return;
-    const int piece = blockIdx.x % a.vsplits;
+    const int piece = unit % a.vsplits;
     const long long per = (a.V + a.vsplits - 1) / a.vsplits;
     const long long v_lo = piece * per;
     const long long v_hi = min(a.V, v_lo + per);
