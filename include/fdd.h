@@ -273,7 +273,7 @@ typedef struct fdd_verify_params {
     float temperature;             /* 0 = greedy verifier, > 0 = sampled verifier */
     const void *ar_logits;         /* [N,B,V] */
     const uint8_t *scaffold_mask;  /* [N,B]; may be NULL */
-    const int32_t *draft;          /* [N,B] draft tokens (read at draft positions only) */
+    const int32_t *draft;          /* [N,B] draft tokens (used at draft positions only) */
     uint8_t *mask;                 /* [N,B] in/out */
     int32_t *tokens;               /* [N,B] in/out */
     int32_t *n_accepted;           /* [N] out; may be NULL */

@@ -445,20 +445,43 @@ __global__ __launch_bounds__(STHREADS) void block_select_kernel(Args a)
     for (int b0 = 0; b0 < a.B; b0 += STHREADS) {     // lane `tid` takes position b0 + tid (ascending per lane)
         const int b = b0 + tid;
         const size_t i = (size_t)n * a.B + (b < a.B ? b : 0);
+        // The first pieces' records are requested together with the mask bytes, not after them: whether the
+        // position is eligible is known one memory round trip later, and the records are then already there.
+        // (records of positions that are not eligible hold whatever an earlier call left; they are not used)
+        constexpr int PRE = 4;
+        const u32x4* pr = reinterpret_cast<const u32x4*>(a.ws + i * a.vsplits);
+        u32x4 rec[PRE];
+#pragma unroll
+        for (int s = 0; s < PRE; ++s) rec[s] = s < a.vsplits ? pr[s] : u32x4{0u, 0u, 0u, 0u};
         const bool eligible = b < a.B && a.mask[i] == 1 && !(a.scaffold && a.scaffold[i]);
         float conf_out = -INFINITY;
         uint8_t com = 0;
         int arg = -1;
         if (eligible) {
+            auto unpack = [](const u32x4& r) {
+                Partial q;
+                q.m = __uint_as_float(r.x); q.arg = (int)r.y; q.s = __uint_as_float(r.z); q.pad = 0;
+                return q;
+            };
             const Partial* p = a.ws + i * a.vsplits;
             // pieces cover ascending index ranges: strict '>' keeps the lowest id
-            float M = p[0].m;
-            arg = p[0].arg;
-            for (int s = 1; s < a.vsplits; ++s)
+            float M = unpack(rec[0]).m;
+            arg = unpack(rec[0]).arg;
+#pragma unroll
+            for (int s = 1; s < PRE; ++s) {
+                const Partial q = unpack(rec[s]);
+                if (s < a.vsplits && q.m > M) { M = q.m; arg = q.arg; }
+            }
+            for (int s = PRE; s < a.vsplits; ++s)
                 if (p[s].m > M) { M = p[s].m; arg = p[s].arg; }
             // sum of the pieces' fp32 sums, rescaled to the row maximum, finished in fp64
             double z = 0.0;
-            for (int s = 0; s < a.vsplits; ++s)
+#pragma unroll
+            for (int s = 0; s < PRE; ++s) {
+                const Partial q = unpack(rec[s]);
+                if (s < a.vsplits && q.s > 0.f) z += (double)(q.s * fast_exp2((q.m - M) * LOG2E));
+            }
+            for (int s = PRE; s < a.vsplits; ++s)
                 if (p[s].s > 0.f) z += (double)(p[s].s * fast_exp2((p[s].m - M) * LOG2E));
             const double conf = 1.0 / z;
             conf_out = (float)conf;
@@ -516,20 +539,31 @@ __global__ __launch_bounds__(STHREADS) void verify_scan_kernel(Args a)
 {
     const int n = blockIdx.x;
     const int tid = threadIdx.x;
-    auto ar_token = [&](size_t i) {
-        const Partial* p = a.ws + i * a.vsplits;
-        float M = p[0].m;
-        int arg = p[0].arg;
-        for (int s = 1; s < a.vsplits; ++s)
-            if (p[s].m > M) { M = p[s].m; arg = p[s].arg; }   // ascending pieces: lowest id on ties
-        return arg;
-    };
-    // pass 1: position of the first mismatch
+    // pass 1: position of the first mismatch, and the AR token there.  A position's records and its draft are
+    // requested together with its mask bytes (one memory round trip instead of three); what was requested for
+    // a position that is no draft is not used.
+    constexpr int PRE = 4;
     int first_bad = 0x7fffffff;
+    int bad_tok = 0;            // AR token at this lane's lowest mismatch
     for (int b = tid; b < a.B; b += STHREADS) {
         const size_t i = (size_t)n * a.B + b;
+        const u32x4* pr = reinterpret_cast<const u32x4*>(a.ws + i * a.vsplits);
+        u32x4 rec[PRE];
+#pragma unroll
+        for (int s = 0; s < PRE; ++s) rec[s] = s < a.vsplits ? pr[s] : u32x4{0u, 0u, 0u, 0u};
+        const int d = a.draft[i];
         const bool is_draft = a.mask[i] == 1 && !(a.scaffold && a.scaffold[i]);
-        if (is_draft && ar_token(i) != a.draft[i] && b < first_bad) first_bad = b;
+        if (!is_draft) continue;
+        // ascending pieces: strict '>' keeps the lowest id on ties
+        float M = __uint_as_float(rec[0].x);
+        int arg = (int)rec[0].y;
+#pragma unroll
+        for (int s = 1; s < PRE; ++s)
+            if (s < a.vsplits && __uint_as_float(rec[s].x) > M) { M = __uint_as_float(rec[s].x); arg = (int)rec[s].y; }
+        const Partial* p = a.ws + i * a.vsplits;
+        for (int s = PRE; s < a.vsplits; ++s)
+            if (p[s].m > M) { M = p[s].m; arg = p[s].arg; }
+        if (arg != d && b < first_bad) { first_bad = b; bad_tok = arg; }
     }
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) first_bad = min(first_bad, __shfl_xor(first_bad, off, 64));
@@ -541,7 +575,8 @@ __global__ __launch_bounds__(STHREADS) void verify_scan_kernel(Args a)
         uint8_t acc = 0;
         if (is_draft && b <= first_bad) {
             acc = (b == first_bad) ? 2 : 1;
-            a.tokens[i] = (b == first_bad) ? ar_token(i) : a.draft[i];
+            // (the lane that visits position first_bad met no mismatch below it: bad_tok is the token there)
+            a.tokens[i] = (b == first_bad) ? bad_tok : a.draft[i];
             a.mask[i] = 0;
             ++count;
         }
