@@ -209,6 +209,9 @@ __global__ __launch_bounds__(RTHREADS) void vocab_reduce_kernel(Args a)
             u32x4 raw[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) raw[u] = __builtin_nontemporal_load(vp + i + u * RTHREADS);
+            // all of them are requested before the first is waited for (left to itself the scheduler waits
+            // for the first after two requests and only then issues the rest: two latencies per group)
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 float x[VEC];
