@@ -161,7 +161,8 @@ def time_spec_verify(F, w, d, g, logits, steps, warmup):
     ws_a = torch.empty(max(256, F.fdd_block_attn_workspace(g["q"], g["prefix_k"], g["prefix_v"], st["block_k"],
                                                            st["block_v"], prefix_v_packed=packed_v)),
                        dtype=torch.uint8, device="cuda")
-    ws_u = torch.empty(max(256, F.fdd_unmask_workspace(logits[0])), dtype=torch.uint8, device="cuda")
+    ws_u = torch.empty(max(256, F.fdd_verify_workspace(logits[0]), F.fdd_verify_workspace(logits[0], temperature=1.0)),
+                       dtype=torch.uint8, device="cuda")
     n_ev = (steps + EVENT_STRIDE - 1) // EVENT_STRIDE       # the event pairs sit on a sample of the passes (see main)
     ev = Events(n_ev)
     v0 = [torch.cuda.Event(enable_timing=True) for _ in range(n_ev)]

@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     fdd_unmask_step,
     fdd_unmask_workspace,
     fdd_verify_step,
+    fdd_verify_workspace,
     fdd_version,
     library_path,
     load_library,

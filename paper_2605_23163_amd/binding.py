@@ -395,6 +395,14 @@ def fdd_unmask_step_static(logits, mask, scaffold_mask, tau, tokens, confidences
     return tokens, confidences, n_unmasked, committed
 
 
+def fdd_verify_workspace(ar_logits, temperature=0.0) -> int:
+    """Workspace bytes of the fdd_verify_step call on these logits (the greedy and the sampled verifier differ)."""
+    p = VerifyParams()
+    p.N, p.B, p.V = ar_logits.shape
+    p.dtype, p.temperature = _dtype_code(ar_logits), float(temperature)
+    return load_library().fdd_verify_workspace(C.byref(p))
+
+
 def fdd_verify_step(ar_logits, mask, scaffold_mask, draft, tokens, n_accepted=None, accepted=None, workspace=None,
                     stream=None, temperature=0.0, seed=0):
     """Accept scan of scaffold speculative decoding; ``tokens`` and ``mask`` are

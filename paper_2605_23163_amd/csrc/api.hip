@@ -347,7 +347,7 @@ size_t fdd_verify_workspace(const fdd_verify_params* p)
 {
     UnmaskPlan plan;
     if (!p || p->V >= (1ll << 31) || (long long)p->N * p->B > (1ll << 24) ||
-        (p->dtype != FDD_F32 && p->dtype != FDD_BF16) || !make_vocab_plan(p->N, p->B, p->V, p->dtype, &plan))
+        (p->dtype != FDD_F32 && p->dtype != FDD_BF16) || !make_vocab_plan(p->N, p->B, p->V, p->dtype, !(p->temperature > 0.f), &plan))
         return 0;
     return plan.ws_bytes;
 }
@@ -365,7 +365,7 @@ fdd_status fdd_verify_step(const fdd_verify_params* p)
         return fail(FDD_ERR_NULL, "fdd_verify_step: ar_logits, draft, mask and tokens must not be NULL");
     if (!aligned16(p->ar_logits)) return fail(FDD_ERR_UNSUPPORTED, "fdd_verify_step: ar_logits must be 16-byte aligned");
     UnmaskPlan plan;
-    make_vocab_plan(p->N, p->B, p->V, p->dtype, &plan);
+    make_vocab_plan(p->N, p->B, p->V, p->dtype, !(p->temperature > 0.f), &plan);
     if (!p->workspace) return fail(FDD_ERR_WORKSPACE, "fdd_verify_step: workspace is NULL, %zu bytes needed", plan.ws_bytes);
     if (reinterpret_cast<uintptr_t>(p->workspace) & 255u) return fail(FDD_ERR_WORKSPACE, "fdd_verify_step: workspace must be 256-byte aligned");
     if (p->workspace_bytes < plan.ws_bytes) return fail(FDD_ERR_WORKSPACE, "fdd_verify_step: workspace has %zu bytes, %zu needed", p->workspace_bytes, plan.ws_bytes);

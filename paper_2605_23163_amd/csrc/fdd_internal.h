@@ -100,7 +100,8 @@ struct UnmaskPlan {
     size_t ws_bytes;  // [N*B][vsplits] x {float max; int32 arg; float sum; int32 pad}
 };
 bool make_unmask_plan(const fdd_unmask_params& p, UnmaskPlan* plan);
-bool make_vocab_plan(int N, int B, long long V, int dtype, UnmaskPlan* plan);
+// `argmax_only`: the plan of the greedy verifier's pass (no sums); the sampled verifier and the unmask step share the other
+bool make_vocab_plan(int N, int B, long long V, int dtype, bool argmax_only, UnmaskPlan* plan);
 hipError_t launch_unmask(const fdd_unmask_params& p, const UnmaskPlan& plan, hipStream_t s);
 hipError_t launch_verify(const fdd_verify_params& p, const UnmaskPlan& plan, hipStream_t s);
 

@@ -17,8 +17,8 @@ hipError_t launch_prefix_pack(const void*, int, int, int, void*, hipStream_t) { 
 hipError_t launch_attn_f32(const fdd_attn_params&, const AttnPlan&, float, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_attn_combine(const fdd_attn_params&, const AttnPlan&, float, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_attn_merge_bf16(const fdd_attn_params&, const AttnPlan&, float, hipStream_t) { ++g_launches; return hipSuccess; }
-bool make_unmask_plan(const fdd_unmask_params& p, UnmaskPlan* plan) { return make_vocab_plan(p.N, p.B, p.V, p.dtype, plan); }
-bool make_vocab_plan(int N, int B, long long V, int, UnmaskPlan* plan)
+bool make_unmask_plan(const fdd_unmask_params& p, UnmaskPlan* plan) { return make_vocab_plan(p.N, p.B, p.V, p.dtype, false, plan); }
+bool make_vocab_plan(int N, int B, long long V, int, bool, UnmaskPlan* plan)
 {
     if (N <= 0 || B <= 0 || V <= 0) return false;
     plan->vsplits = 2;
