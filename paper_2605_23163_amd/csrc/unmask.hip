@@ -146,12 +146,14 @@ __device__ __forceinline__ float bf16_to_f32(uint32_t bits16) { return __uint_as
 // not eligible leaves at once.  With (row, piece) = (index / vsplits, index % vsplits) an XCD
 // would always get rows of the same residue, and a scaffold pattern that repeats from rollout
 // to rollout (it does: the schema is shared) would load the XCDs unequally.  So each group of 8
-// consecutive indices is rotated by its own number: over the groups every XCD meets every residue.
+// consecutive indices is rotated, by an amount that changes from group to group, from 8 groups to the
+// next 8 and from 64 to the next 64 (a rotation by the group's number alone repeats with the pattern:
+// config 5's 720 eligible rows of 4 pieces then give the XCDs 304..416 workgroups instead of 360 each).
 __device__ __forceinline__ unsigned unit_of_workgroup()
 {
     const unsigned u = blockIdx.x, g = u >> 3;
     if ((g << 3) + 8u > gridDim.x) return u;           // a last, incomplete group stays as it is
-    return (g << 3) + ((u + g) & 7u);
+    return (g << 3) + ((u + g + (g >> 3) + (g >> 6) + (g >> 9)) & 7u);
 }
 
 // T = uint16_t (bf16 bits) or float; SUM = false leaves (max, arg max) only and a sum of 0
