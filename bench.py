@@ -51,7 +51,7 @@ STEPS_PER_BLOCK = 8
 # counters cannot be read from inside this process, so the line quotes the figure and says where it is from.
 # (read MiB, write MiB) per launch.
 MEASURED_TRAFFIC_MIB = {"cfg5": {"attn_bf16_kernel": (48.7, 15.3), "vocab_reduce_kernel": (192.9, 0.1)}}
-TRAFFIC_SOURCE = "profiles/bench_cfg5_denoise_step.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; build of commit 7ff2e0a)"
+TRAFFIC_SOURCE = "profiles/bench_cfg5_denoise_step.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; build of commit 41205d4)"
 PREHEAT_MS = 80.0          # untimed GPU load before the timed region: the shader clock takes about 30 ms to settle
 MIN_ATTN_SAMPLES = 20      # the attention kernel is timed on at least this many launches
 
