@@ -284,6 +284,8 @@ typedef struct fdd_verify_params {
     uint64_t seed;                 /* sampled verifier: key of the random stream */
 } fdd_verify_params;
 
+/* Bytes of scratch for these params (host-only arithmetic; 0 if they are invalid).  The figure depends on
+ * `temperature`: the greedy verifier cuts a row into more pieces than the sampled one. */
 size_t fdd_verify_workspace(const fdd_verify_params *p);
 fdd_status fdd_verify_step(const fdd_verify_params *p);
 
