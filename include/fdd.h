@@ -177,6 +177,12 @@ fdd_status fdd_prefix_pack(const void *prefix_v, int32_t L, int32_t Hkv, int32_t
  *
  * Only the logits rows of eligible positions are read.  The arg max is taken
  * on the stored logits (exact); exp and the sum run in fp32.
+ *
+ * Logits: finite values, and -inf for entries that can never be chosen (their
+ * probability is exactly 0; a row needs at least one finite entry).  NaN and
+ * +inf are not supported: the outputs of a row that holds one are undefined
+ * (nothing is read or written out of bounds).  The same holds for the logits
+ * of fdd_verify_step.
  */
 typedef struct fdd_unmask_params {
     int32_t N, B;
